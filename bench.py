@@ -1,0 +1,163 @@
+#!/usr/bin/env python3
+"""Benchmark of the MLA decode hot path on one MI355X.
+
+A "step" is one whole call of the path (split-KV main kernel + LSE combine kernel) over one batch
+of seeded synthetic input that is already resident in HBM.  The workload is the configuration the
+headline metric is quoted on: batch 16, 16 heads, KV length 65536 per sequence, bf16.
+
+Prints ONE JSON line.  `value` is algorithmic bytes per call / wall time per call (TB/s);
+`roofline` is the main kernel alone, timed with events on the launch stream; `cpu_baseline` is
+the fp64 oracle timed on this machine's host cores over a bounded sample of the same workload.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+METRIC = "MLA decode us/call + achieved HBM TB/s (b=16, 16 heads, KV=64K, bf16)"
+HBM_PEAK_GBPS = 8000.0          # MI355X published peak
+TRAFFIC_FILE = os.path.join(ROOT, "profiles", "mla_decode_split_b16_kv64k_traffic.json")
+CPU_SAMPLE_SEQS = 16            # sequences of the batch the oracle is timed on (about 15 s of CPU work)
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--config", type=int, default=4, help="benchmark configuration id (4 = headline)")
+    ap.add_argument("--chunk-len", type=int, default=0, help="force the split plan (0 = automatic)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build is a single-GPU kernel library; run with --gpus 1 "
+              "(no sharding, collectives or multi-rank path exists)", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2506_01969_amd import inputs, mla
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(1)
+    mla.lib()                                   # fail loudly if the HIP library is missing
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+
+    cfg = inputs.CONFIGS[args.config]
+    q, kv, lens = inputs.make_config(args.config)
+    batch, max_seqlen = cfg["batch"], cfg["seqlen"]
+    alg_bytes = inputs.algorithmic_bytes(lens.tolist())
+    alg_flops = inputs.algorithmic_flops(lens.tolist())
+
+    qd, ld = q.to(dev), lens.to(dev)
+    kv_bytes = kv.numel() * 2
+    # rotate over enough KV copies that no call can be served from the 256 MB last-level cache
+    n_buf = max(2, -(-(512 << 20) // kv_bytes))
+    kvs = [kv.to(dev)]
+    for _ in range(n_buf - 1):
+        kvs.append(kvs[0].clone())
+    chunk = args.chunk_len or None
+    if chunk is None:
+        need, chunk_used, splits = mla.mla_decode_workspace_size(batch, 16, max_seqlen, 0)
+    else:
+        need, splits = mla.mla_decode_workspace_size_for_chunk(batch, max_seqlen, chunk)
+        chunk_used = chunk
+    ws = torch.empty((need,), dtype=torch.uint8, device=dev)
+    out = torch.empty((batch, 1, 16, 512), dtype=torch.float32, device=dev)
+    lse = torch.empty((batch, 16), dtype=torch.float32, device=dev)
+
+    def step(i, phases=None):
+        mla.mla_decode(qd, kvs[i % n_buf], ld, inputs.SCALE, out=out, lse=lse, workspace=ws,
+                       chunk_len=chunk, phases=phases)
+
+    # ---- whole call ----------------------------------------------------------------------------
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(i)
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    ms_per_step = wall / args.steps * 1e3
+    tbps = alg_bytes / (ms_per_step * 1e-3) / 1e12
+
+    # ---- main kernel alone, events on the launch stream (torch's current stream) ---------------
+    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
+    for i in range(min(args.warmup, 5)):
+        step(i, mla.PHASE_SPLIT)
+    torch.cuda.synchronize()
+    for i in range(args.steps):
+        ev[i][0].record()
+        step(i, mla.PHASE_SPLIT)
+        ev[i][1].record()
+    torch.cuda.synchronize()
+    durs = sorted(a.elapsed_time(b) for a, b in ev)
+    split_ms_avg = sum(durs) / len(durs)
+    split_ms_med = durs[len(durs) // 2]
+    # combine alone, for the record
+    evc = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
+    for i in range(args.steps):
+        evc[i][0].record()
+        step(i, mla.PHASE_COMBINE)
+        evc[i][1].record()
+    torch.cuda.synchronize()
+    comb_ms_avg = sum(a.elapsed_time(b) for a, b in evc) / len(evc)
+    achieved_gbps = alg_bytes / (split_ms_avg * 1e-3) / 1e9
+
+    traffic = None
+    if args.config == 4 and os.path.exists(TRAFFIC_FILE):
+        try:
+            traffic = json.load(open(TRAFFIC_FILE)).get("hbm_bytes_per_launch")
+        except (OSError, ValueError):
+            traffic = None
+
+    # ---- CPU baseline: the oracle as it stands, on a bounded sample ----------------------------
+    cpu = None
+    if not args.no_cpu_baseline:
+        from oracle import mla_oracle
+        ns = min(CPU_SAMPLE_SEQS, batch)
+        qs, kvsamp, ls = q[:ns], kv[:ns], lens[:ns]
+        qb, kvb = inputs.bf16_bits(qs), inputs.bf16_bits(kvsamp)
+        t0 = time.perf_counter()
+        ref_o, ref_l = mla_oracle.decode(qb, kvb, ls.numpy(), inputs.SCALE, inputs.D_V)
+        cpu_s = time.perf_counter() - t0
+        sample_bytes = inputs.algorithmic_bytes(ls.tolist())
+        # the same sample doubles as a sanity check of the benchmarked output
+        got = out.cpu().numpy().reshape(batch, 16, 512)[:ns]
+        max_abs = float(abs(got - ref_o).max())
+        cpu = {"value": sample_bytes / cpu_s / 1e12, "unit": "TB/s", "cores": mla_oracle.threads(), "kind": "oracle",
+               "sample": "first %d of %d sequences, all 16 heads, full KV (%d tokens), one oracle call" % (
+                   ns, batch, int(ls.sum())),
+               "seconds": cpu_s, "us_per_call_equiv": cpu_s * 1e6 * (alg_bytes / sample_bytes),
+               "gpu_vs_oracle_max_abs_on_sample": max_abs}
+
+    line = {
+        "metric": METRIC, "value": tbps, "unit": "TB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step, "us_per_call": ms_per_step * 1e3, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "config %d: MLA decode batch %d, q_len 1, 16 heads, shared 576-d bf16 latent KV, "
+                               "KV length %s, scale 1/sqrt(192), d_v 512" % (
+                                   args.config, batch, "%d per sequence" % max_seqlen if cfg["ragged"] is None
+                                   else "ragged uniform[%d,%d]" % cfg["ragged"]),
+                   "total_kv_tokens": int(lens.sum()), "algorithmic_bytes_per_call": alg_bytes,
+                   "algorithmic_flops_per_call": alg_flops, "chunk_len": chunk_used, "splits_max": splits,
+                   "kv_buffers_rotated": n_buf, "hbm_peak_frac_whole_call": tbps * 1e3 / HBM_PEAK_GBPS,
+                   "tflops_whole_call": alg_flops / (ms_per_step * 1e-3) / 1e12},
+        "roofline": {"bound": "hbm", "kernel": "mla_decode_split_kernel", "achieved": achieved_gbps,
+                     "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": achieved_gbps / HBM_PEAK_GBPS, "traffic": traffic,
+                     "avg_us": split_ms_avg * 1e3, "median_us": split_ms_med * 1e3,
+                     "combine_kernel_avg_us": comb_ms_avg * 1e3},
+        "cpu_baseline": cpu,
+    }
+    print(json.dumps(line))
+
+
+if __name__ == "__main__":
+    main()

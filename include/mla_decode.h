@@ -1,0 +1,124 @@
+/*
+ * mla_decode.h -- C ABI of the MI355X (gfx950) MLA decode-attention library.
+ *
+ * The operation is the per-head attention of the paper's Section 3.1
+ * ("Original MLA Computation Mode in Inference"), S = Q K^T, P = softmax(S),
+ * O = P V, for one query token per sequence (the decoding setup of Section 4.1:
+ * 16 heads, head dimension 576), together with the log-sum-exp L = m + log(l)
+ * that Algorithm 1 writes in its last step.  In MLA all heads share ONE latent
+ * KV row per token, and V is the first 512 columns of that row.
+ *
+ * On the device the work is cut along the KV length into chunks (one workgroup
+ * per sequence and chunk), each chunk runs the block-wise online-softmax
+ * recurrence of Algorithm 1 in the transposed orientation of equations (1)-(4)
+ * (KV tokens on the matrix-core M axis), and a second kernel merges the chunk
+ * results by log-sum-exp.  The paper has no split over KV; it is the same
+ * m / l recurrence applied across chunks.
+ *
+ * Conventions for every entry point
+ *   - plain C types only; "device" pointers are HIP device pointers, "host"
+ *     pointers are ordinary process memory;
+ *   - the caller owns every buffer; the library never allocates, frees or
+ *     synchronises; mla_decode() is asynchronous on the given stream;
+ *   - every host-detectable error is reported BEFORE anything is launched and
+ *     leaves the outputs untouched; no exceptions, no global mutable state
+ *     visible to the caller; entry points may be called from several threads.
+ */
+#ifndef MLA_DECODE_H
+#define MLA_DECODE_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    MLA_OK = 0,
+    MLA_ERR_INVALID_ARG = 1,         /* null / misaligned pointer, negative size or stride      */
+    MLA_ERR_UNSUPPORTED_SHAPE = 2,   /* anything but 16 heads, d_qk 576, d_v 512, q_len 1       */
+    MLA_ERR_WORKSPACE_TOO_SMALL = 3, /* workspace_bytes below mla_decode_workspace_size()       */
+    MLA_ERR_HIP = 4                  /* a HIP runtime call or a kernel launch failed            */
+} mla_status_t;
+
+/* Fixed problem shape (DeepSeek-R1 share of one GPU, Section 4.1). */
+#define MLA_NUM_HEADS 16
+#define MLA_D_QK 576
+#define MLA_D_V 512
+
+/*
+ * Split plan and workspace size.  Host only, deterministic, touches no device
+ * unless num_cus == 0 (then the compute-unit count of the current HIP device is
+ * queried).  The plan depends only on (batch, max_seqlen_kv, num_cus), never on
+ * the per-sequence lengths, which live on the device.
+ *
+ *   batch          >= 1 sequences
+ *   num_heads      must be MLA_NUM_HEADS
+ *   max_seqlen_kv  >= 1, rows allocated per sequence in the KV cache
+ *   num_cus        compute units to fill; 0 = ask the current device
+ *   bytes          [out, host] workspace size mla_decode() needs (may be 0 splits -> still > 0)
+ *   chunk_len      [out, host, may be NULL] KV tokens per workgroup
+ *   num_splits_max [out, host, may be NULL] ceil(max_seqlen_kv / chunk_len)
+ */
+mla_status_t mla_decode_workspace_size(int batch, int num_heads, int max_seqlen_kv, int num_cus,
+                                       size_t *bytes, int *chunk_len, int *num_splits_max);
+
+/*
+ * One decode-attention call.
+ *
+ *   q               device, bf16 [batch][1][16][576], contiguous, 16-byte aligned
+ *   kv_cache        device, bf16; sequence b starts at kv_cache + b*kv_batch_stride
+ *                   elements; each token is one row of 576 contiguous bf16 (K = the
+ *                   whole row, V = its first 512 columns); 16-byte aligned
+ *   kv_batch_stride elements between sequences, >= max_seqlen_kv*576, multiple of 8
+ *   cache_seqlens   device, int32 [batch]; values are clamped to [0, max_seqlen_kv]
+ *                   on the device; rows at or beyond a sequence's length are never
+ *                   read into the result
+ *   batch, num_heads, max_seqlen_kv   as above
+ *   scale           multiplies q.k before the softmax (1/sqrt(192) for DeepSeek-R1)
+ *   out             device, fp32 [batch][1][16][512], contiguous, 16-byte aligned
+ *   lse             device, fp32 [batch][16]: natural log of sum_t exp(scale * q.k_t)
+ *   workspace       device, 16-byte aligned, >= mla_decode_workspace_size() bytes;
+ *                   contents on entry are irrelevant, contents on exit unspecified
+ *   stream          hipStream_t (as void*), NULL = the default stream
+ *
+ * A sequence of length 0 yields out = 0 and lse = -inf.
+ * Two calls that share a workspace must be ordered on the same stream.
+ */
+mla_status_t mla_decode(const void *q, const void *kv_cache, int64_t kv_batch_stride,
+                        const int32_t *cache_seqlens, int batch, int num_heads,
+                        int max_seqlen_kv, float scale, float *out, float *lse,
+                        void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * Extended call for tuning sweeps, tests of the log-sum-exp merge and per-kernel timing.
+ *   chunk_len  0 = the automatic plan of mla_decode(); otherwise a positive multiple of
+ *              MLA_CHUNK_GRANULE KV tokens per workgroup.  With a forced chunk the workspace
+ *              must hold mla_decode_workspace_size_for_chunk() bytes.
+ *   phases     MLA_PHASE_SPLIT launches the split-KV main kernel (every step of Algorithm 1
+ *              on each chunk), MLA_PHASE_COMBINE launches the merge of the chunk results;
+ *              mla_decode() is both.  Running the combine phase alone is only meaningful
+ *              after a split phase with the same arguments and workspace.
+ * All other arguments, and all error behaviour, are those of mla_decode().
+ */
+#define MLA_CHUNK_GRANULE 128
+#define MLA_PHASE_SPLIT 1
+#define MLA_PHASE_COMBINE 2
+mla_status_t mla_decode_ex(const void *q, const void *kv_cache, int64_t kv_batch_stride,
+                           const int32_t *cache_seqlens, int batch, int num_heads,
+                           int max_seqlen_kv, float scale, float *out, float *lse,
+                           void *workspace, size_t workspace_bytes, int chunk_len, int phases,
+                           void *stream);
+
+/* Workspace size for a forced chunk length (host only, no device access). */
+mla_status_t mla_decode_workspace_size_for_chunk(int batch, int max_seqlen_kv, int chunk_len,
+                                                 size_t *bytes, int *num_splits_max);
+
+/* Static string for a status code (never NULL). */
+const char *mla_status_string(mla_status_t status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MLA_DECODE_H */

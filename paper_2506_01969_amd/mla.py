@@ -1,0 +1,138 @@
+"""Thin Python binding of the C ABI in ``include/mla_decode.h`` (argument marshalling only).
+
+Every step of the computation runs inside ``libmla_decode.so``; torch is used for device
+memory and the current stream, nothing else.  There is no fallback: if the library is
+missing or fails to load, importing callers get an error.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+import torch
+
+NUM_HEADS = 16
+D_QK = 576
+D_V = 512
+
+MLA_OK = 0
+MLA_ERR_INVALID_ARG = 1
+MLA_ERR_UNSUPPORTED_SHAPE = 2
+MLA_ERR_WORKSPACE_TOO_SMALL = 3
+MLA_ERR_HIP = 4
+
+LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libmla_decode.so")
+_lib = None
+
+
+class MlaError(RuntimeError):
+    def __init__(self, status, where):
+        self.status = int(status)
+        msg = lib().mla_status_string(self.status).decode()
+        super().__init__("%s: %s (status %d)" % (where, msg, self.status))
+
+
+def lib():
+    """Load ``libmla_decode.so`` (built by ``paper_2506_01969_amd.build``); raises if absent."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(
+                "%s not found: run `python -c 'import __graft_entry__ as g; g.build()'` first" % LIB_PATH)
+        L = ctypes.CDLL(LIB_PATH)
+        vp, ci, sz = ctypes.c_void_p, ctypes.c_int, ctypes.c_size_t
+        szp, cip = ctypes.POINTER(ctypes.c_size_t), ctypes.POINTER(ctypes.c_int)
+        L.mla_decode_workspace_size.argtypes = [ci, ci, ci, ci, szp, cip, cip]
+        L.mla_decode_workspace_size.restype = ci
+        L.mla_decode_workspace_size_for_chunk.argtypes = [ci, ci, ci, szp, cip]
+        L.mla_decode_workspace_size_for_chunk.restype = ci
+        L.mla_decode.argtypes = [vp, vp, ctypes.c_int64, vp, ci, ci, ci, ctypes.c_float, vp, vp, vp, sz, vp]
+        L.mla_decode.restype = ci
+        L.mla_decode_ex.argtypes = [vp, vp, ctypes.c_int64, vp, ci, ci, ci, ctypes.c_float, vp, vp,
+                                    vp, sz, ci, ci, vp]
+        L.mla_decode_ex.restype = ci
+        L.mla_status_string.argtypes = [ci]
+        L.mla_status_string.restype = ctypes.c_char_p
+        _lib = L
+    return _lib
+
+
+def mla_decode_workspace_size(batch, num_heads, max_seqlen_kv, num_cus=0):
+    """-> (bytes, chunk_len, num_splits_max).  num_cus=0 asks the current device."""
+    nbytes, chunk, splits = ctypes.c_size_t(0), ctypes.c_int(0), ctypes.c_int(0)
+    st = lib().mla_decode_workspace_size(batch, num_heads, max_seqlen_kv, num_cus,
+                                         ctypes.byref(nbytes), ctypes.byref(chunk), ctypes.byref(splits))
+    if st != MLA_OK:
+        raise MlaError(st, "mla_decode_workspace_size")
+    return nbytes.value, chunk.value, splits.value
+
+
+def mla_decode_workspace_size_for_chunk(batch, max_seqlen_kv, chunk_len):
+    """-> (bytes, num_splits_max) for a forced chunk length."""
+    nbytes, splits = ctypes.c_size_t(0), ctypes.c_int(0)
+    st = lib().mla_decode_workspace_size_for_chunk(batch, max_seqlen_kv, chunk_len,
+                                                   ctypes.byref(nbytes), ctypes.byref(splits))
+    if st != MLA_OK:
+        raise MlaError(st, "mla_decode_workspace_size_for_chunk")
+    return nbytes.value, splits.value
+
+
+def _check_tensors(q, kv_cache, cache_seqlens):
+    if q.dtype != torch.bfloat16 or kv_cache.dtype != torch.bfloat16:
+        raise TypeError("q and kv_cache must be bf16")
+    if cache_seqlens.dtype != torch.int32:
+        raise TypeError("cache_seqlens must be int32")
+    if not (q.is_cuda and kv_cache.is_cuda and cache_seqlens.is_cuda):
+        raise ValueError("q, kv_cache and cache_seqlens must be device tensors")
+    if q.dim() != 4 or q.shape[1] != 1 or q.shape[3] != D_QK or not q.is_contiguous():
+        raise ValueError("q must be contiguous [batch, 1, heads, 576]")
+    if kv_cache.dim() != 3 or kv_cache.shape[0] != q.shape[0] or kv_cache.shape[2] != D_QK:
+        raise ValueError("kv_cache must be [batch, max_seqlen_kv, 576]")
+    if kv_cache.stride(2) != 1 or kv_cache.stride(1) != D_QK:
+        raise ValueError("kv_cache rows must be contiguous (row stride 576)")
+    if cache_seqlens.shape != (q.shape[0],) or not cache_seqlens.is_contiguous():
+        raise ValueError("cache_seqlens must be contiguous [batch]")
+
+
+PHASE_SPLIT = 1
+PHASE_COMBINE = 2
+
+
+def mla_decode(q, kv_cache, cache_seqlens, scale, out=None, lse=None, workspace=None, chunk_len=None,
+               phases=None):
+    """out [batch, 1, heads, 512] fp32, lse [batch, heads] fp32 on the current stream (asynchronous).
+
+    q [batch, 1, 16, 576] bf16, kv_cache [batch, max_seqlen_kv, 576] bf16 (batch stride free),
+    cache_seqlens [batch] int32, all on the current device.  ``out``, ``lse`` and ``workspace``
+    (a uint8 tensor) are allocated with torch when not given.  ``chunk_len`` forces the split plan
+    and ``phases`` selects the kernels (both go through ``mla_decode_ex``).
+    """
+    _check_tensors(q, kv_cache, cache_seqlens)
+    batch, _, heads, _ = q.shape
+    max_seqlen = kv_cache.shape[1]
+    dev = q.device
+    if chunk_len is None:
+        need, _, _ = mla_decode_workspace_size(batch, heads, max_seqlen, 0)
+    else:
+        need, _ = mla_decode_workspace_size_for_chunk(batch, max_seqlen, chunk_len)
+    if out is None:
+        out = torch.empty((batch, 1, heads, D_V), dtype=torch.float32, device=dev)
+    if lse is None:
+        lse = torch.empty((batch, heads), dtype=torch.float32, device=dev)
+    if workspace is None:
+        workspace = torch.empty((need,), dtype=torch.uint8, device=dev)
+    stream = ctypes.c_void_p(torch.cuda.current_stream(dev).cuda_stream)
+    args = [ctypes.c_void_p(q.data_ptr()), ctypes.c_void_p(kv_cache.data_ptr()), kv_cache.stride(0),
+            ctypes.c_void_p(cache_seqlens.data_ptr()), batch, heads, max_seqlen, float(scale),
+            ctypes.c_void_p(out.data_ptr()), ctypes.c_void_p(lse.data_ptr()),
+            ctypes.c_void_p(workspace.data_ptr()), workspace.numel() * workspace.element_size()]
+    if chunk_len is None and phases is None:
+        st = lib().mla_decode(*args, stream)
+        where = "mla_decode"
+    else:
+        st = lib().mla_decode_ex(*args, int(chunk_len or 0),
+                                 int(PHASE_SPLIT | PHASE_COMBINE if phases is None else phases), stream)
+        where = "mla_decode_ex"
+    if st != MLA_OK:
+        raise MlaError(st, where)
+    return out, lse

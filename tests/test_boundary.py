@@ -1,0 +1,115 @@
+"""Host-side checks of the C ABI that need no GPU: the library loads, exports every symbol the
+header declares, the split plan is sane, and every host-detectable error is reported before any
+device work (fake but well-aligned pointers are never dereferenced on these paths)."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2506_01969_amd import mla
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared_functions():
+    text = open(os.path.join(ROOT, "include", "mla_decode.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(mla_[a-z_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    names = _declared_functions()
+    assert {"mla_decode", "mla_decode_ex", "mla_decode_workspace_size",
+            "mla_decode_workspace_size_for_chunk", "mla_status_string"} <= set(names)
+    lib = mla.lib()
+    for n in names:
+        assert hasattr(lib, n), n
+
+
+def test_status_strings():
+    lib = mla.lib()
+    seen = {lib.mla_status_string(i) for i in range(5)}
+    assert len(seen) == 5 and all(seen)
+    assert lib.mla_status_string(99)
+
+
+@pytest.mark.parametrize("batch,seqlen", [(1, 512), (16, 4096), (16, 16384), (16, 65536), (32, 65536), (1, 1), (3, 100000)])
+def test_plan_covers_the_sequence_and_fills_the_cus(batch, seqlen):
+    nbytes, chunk, splits = mla.mla_decode_workspace_size(batch, 16, seqlen, num_cus=256)
+    assert chunk % 128 == 0 and chunk >= 128
+    assert (splits - 1) * chunk < seqlen <= splits * chunk
+    per_split = 16 * 512 * 4 + 16 * 4
+    assert nbytes >= batch * splits * per_split
+    assert nbytes <= batch * splits * per_split + 16
+    # enough workgroups for 256 compute units whenever the problem is large enough
+    if batch * seqlen >= 256 * 512:
+        assert batch * splits >= 256
+    nb2, sp2 = mla.mla_decode_workspace_size_for_chunk(batch, seqlen, chunk)
+    assert (nb2, sp2) == (nbytes, splits)
+
+
+def test_plan_is_deterministic_and_scales_with_cus():
+    a = mla.mla_decode_workspace_size(16, 16, 65536, num_cus=256)
+    b = mla.mla_decode_workspace_size(16, 16, 65536, num_cus=256)
+    c = mla.mla_decode_workspace_size(16, 16, 65536, num_cus=64)
+    assert a == b
+    assert c[1] >= a[1]          # fewer compute units -> longer chunks
+
+
+def test_workspace_size_errors():
+    lib = mla.lib()
+    n = ctypes.c_size_t(0)
+    assert lib.mla_decode_workspace_size(16, 8, 4096, 256, ctypes.byref(n), None, None) == mla.MLA_ERR_UNSUPPORTED_SHAPE
+    assert lib.mla_decode_workspace_size(0, 16, 4096, 256, ctypes.byref(n), None, None) == mla.MLA_ERR_INVALID_ARG
+    assert lib.mla_decode_workspace_size(16, 16, 0, 256, ctypes.byref(n), None, None) == mla.MLA_ERR_INVALID_ARG
+    assert lib.mla_decode_workspace_size(16, 16, 4096, -1, ctypes.byref(n), None, None) == mla.MLA_ERR_INVALID_ARG
+    assert lib.mla_decode_workspace_size(16, 16, 4096, 256, None, None, None) == mla.MLA_ERR_INVALID_ARG
+    assert lib.mla_decode_workspace_size_for_chunk(16, 4096, 100, ctypes.byref(n), None) == mla.MLA_ERR_INVALID_ARG
+    assert lib.mla_decode_workspace_size_for_chunk(16, 4096, 0, ctypes.byref(n), None) == mla.MLA_ERR_INVALID_ARG
+
+
+def _call(q=0x1000, kv=0x2000, stride=4096 * 576, lens=0x3000, batch=2, heads=16, seqlen=4096, scale=0.1,
+          out=0x4000, lse=0x5000, ws=0x6000, ws_bytes=1 << 30, chunk=256, phases=3):
+    vp = ctypes.c_void_p
+    return mla.lib().mla_decode_ex(vp(q), vp(kv), stride, vp(lens), batch, heads, seqlen, scale, vp(out), vp(lse),
+                                   vp(ws), ws_bytes, chunk, phases, None)
+
+
+def test_decode_argument_errors_come_before_any_device_work():
+    E = mla
+    assert _call(q=0) == E.MLA_ERR_INVALID_ARG
+    assert _call(kv=0) == E.MLA_ERR_INVALID_ARG
+    assert _call(lens=0) == E.MLA_ERR_INVALID_ARG
+    assert _call(out=0) == E.MLA_ERR_INVALID_ARG
+    assert _call(lse=0) == E.MLA_ERR_INVALID_ARG
+    assert _call(ws=0) == E.MLA_ERR_INVALID_ARG
+    assert _call(q=0x1008) == E.MLA_ERR_INVALID_ARG          # misaligned
+    assert _call(kv=0x2004) == E.MLA_ERR_INVALID_ARG
+    assert _call(out=0x4002) == E.MLA_ERR_INVALID_ARG
+    assert _call(lse=0x5001) == E.MLA_ERR_INVALID_ARG
+    assert _call(heads=8) == E.MLA_ERR_UNSUPPORTED_SHAPE
+    assert _call(heads=128) == E.MLA_ERR_UNSUPPORTED_SHAPE
+    assert _call(batch=0) == E.MLA_ERR_INVALID_ARG
+    assert _call(seqlen=-5) == E.MLA_ERR_INVALID_ARG
+    assert _call(stride=4095 * 576) == E.MLA_ERR_INVALID_ARG   # rows of one sequence would overlap the next
+    assert _call(stride=4096 * 576 + 4) == E.MLA_ERR_INVALID_ARG  # breaks 16-byte alignment of rows
+    assert _call(scale=float("nan")) == E.MLA_ERR_INVALID_ARG
+    assert _call(scale=float("inf")) == E.MLA_ERR_INVALID_ARG
+    assert _call(chunk=100) == E.MLA_ERR_INVALID_ARG
+    assert _call(chunk=-128) == E.MLA_ERR_INVALID_ARG
+    assert _call(phases=0) == E.MLA_ERR_INVALID_ARG
+    assert _call(phases=4) == E.MLA_ERR_INVALID_ARG
+    need, _ = mla.mla_decode_workspace_size_for_chunk(2, 4096, 256)
+    assert _call(ws_bytes=need - 1) == E.MLA_ERR_WORKSPACE_TOO_SMALL
+
+
+def test_binding_rejects_host_tensors():
+    import torch
+    q = torch.zeros((1, 1, 16, 576), dtype=torch.bfloat16)
+    kv = torch.zeros((1, 8, 576), dtype=torch.bfloat16)
+    lens = torch.zeros((1,), dtype=torch.int32)
+    with pytest.raises(ValueError):
+        mla.mla_decode(q, kv, lens, 0.1)
+    with pytest.raises(TypeError):
+        mla.mla_decode(q.float(), kv, lens, 0.1)
