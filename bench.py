@@ -31,8 +31,11 @@ def main():
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--config", type=int, default=4, help="benchmark configuration id (4 = headline)")
-    ap.add_argument("--chunk-len", type=int, default=0, help="force the split plan (0 = automatic)")
+    ap.add_argument("--workgroups", type=int, default=0, help="force the number of workgroups (0 = automatic)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="only run a plain device-to-device copy of 1 GiB five times (counter calibration "
+                         "for rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE) and exit")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build is a single-GPU kernel library; run with --gpus 1 "
@@ -49,6 +52,16 @@ def main():
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
 
+    if args.copy_calibration:
+        src = torch.full((1 << 28,), 1.0, dtype=torch.float32, device=dev)     # 1 GiB
+        dst = torch.empty_like(src)
+        for _ in range(5):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_calibration_bytes_read": src.numel() * 4, "copy_calibration_bytes_written": src.numel() * 4,
+                          "copies": 5}))
+        return
+
     cfg = inputs.CONFIGS[args.config]
     q, kv, lens = inputs.make_config(args.config)
     batch, max_seqlen = cfg["batch"], cfg["seqlen"]
@@ -62,19 +75,15 @@ def main():
     kvs = [kv.to(dev)]
     for _ in range(n_buf - 1):
         kvs.append(kvs[0].clone())
-    chunk = args.chunk_len or None
-    if chunk is None:
-        need, chunk_used, splits = mla.mla_decode_workspace_size(batch, 16, max_seqlen, 0)
-    else:
-        need, splits = mla.mla_decode_workspace_size_for_chunk(batch, max_seqlen, chunk)
-        chunk_used = chunk
+    nwg = args.workgroups or None
+    need, nwg_used = mla.mla_decode_workspace_size(batch, 16, max_seqlen, args.workgroups)
     ws = torch.empty((need,), dtype=torch.uint8, device=dev)
     out = torch.empty((batch, 1, 16, 512), dtype=torch.float32, device=dev)
     lse = torch.empty((batch, 16), dtype=torch.float32, device=dev)
 
     def step(i, phases=None):
         mla.mla_decode(qd, kvs[i % n_buf], ld, inputs.SCALE, out=out, lse=lse, workspace=ws,
-                       chunk_len=chunk, phases=phases)
+                       num_workgroups=nwg, phases=phases)
 
     # ---- whole call ----------------------------------------------------------------------------
     for i in range(args.warmup):
@@ -147,7 +156,7 @@ def main():
                                    args.config, batch, "%d per sequence" % max_seqlen if cfg["ragged"] is None
                                    else "ragged uniform[%d,%d]" % cfg["ragged"]),
                    "total_kv_tokens": int(lens.sum()), "algorithmic_bytes_per_call": alg_bytes,
-                   "algorithmic_flops_per_call": alg_flops, "chunk_len": chunk_used, "splits_max": splits,
+                   "algorithmic_flops_per_call": alg_flops, "workgroups": nwg_used,
                    "kv_buffers_rotated": n_buf, "hbm_peak_frac_whole_call": tbps * 1e3 / HBM_PEAK_GBPS,
                    "tflops_whole_call": alg_flops / (ms_per_step * 1e-3) / 1e12},
         "roofline": {"bound": "hbm", "kernel": "mla_decode_split_kernel", "achieved": achieved_gbps,

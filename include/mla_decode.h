@@ -8,12 +8,14 @@
  * that Algorithm 1 writes in its last step.  In MLA all heads share ONE latent
  * KV row per token, and V is the first 512 columns of that row.
  *
- * On the device the work is cut along the KV length into chunks (one workgroup
- * per sequence and chunk), each chunk runs the block-wise online-softmax
- * recurrence of Algorithm 1 in the transposed orientation of equations (1)-(4)
- * (KV tokens on the matrix-core M axis), and a second kernel merges the chunk
- * results by log-sum-exp.  The paper has no split over KV; it is the same
- * m / l recurrence applied across chunks.
+ * On the device the KV rows of all sequences form one stream of 128-token units
+ * that is divided evenly over a persistent grid of workgroups (so ragged batches
+ * are balanced, and results are bit-identical from run to run); each workgroup runs the block-wise online-softmax recurrence of
+ * Algorithm 1 on its pieces in the transposed orientation of equations (1)-(4)
+ * (KV tokens on the matrix-core M axis), and a second kernel merges, by
+ * log-sum-exp, the pieces of every sequence that several workgroups shared.  The
+ * paper has no split over KV; the merge is the same m / l recurrence applied
+ * across workgroups.
  *
  * Conventions for every entry point
  *   - plain C types only; "device" pointers are HIP device pointers, "host"
@@ -48,21 +50,23 @@ typedef enum {
 #define MLA_D_V 512
 
 /*
- * Split plan and workspace size.  Host only, deterministic, touches no device
- * unless num_cus == 0 (then the compute-unit count of the current HIP device is
- * queried).  The plan depends only on (batch, max_seqlen_kv, num_cus), never on
- * the per-sequence lengths, which live on the device.
+ * Workspace size.  Host only, deterministic, touches no device unless
+ * num_workgroups == 0 (then the compute-unit count of the current HIP device is
+ * queried: the automatic plan is a persistent workgroup on 11 of every 16 compute
+ * units, which is where HBM saturates).
+ * The size depends only on (batch, number of workgroups), never on the
+ * per-sequence lengths, which live on the device.
  *
- *   batch          >= 1 sequences
- *   num_heads      must be MLA_NUM_HEADS
- *   max_seqlen_kv  >= 1, rows allocated per sequence in the KV cache
- *   num_cus        compute units to fill; 0 = ask the current device
- *   bytes          [out, host] workspace size mla_decode() needs (may be 0 splits -> still > 0)
- *   chunk_len      [out, host, may be NULL] KV tokens per workgroup
- *   num_splits_max [out, host, may be NULL] ceil(max_seqlen_kv / chunk_len)
+ *   batch                >= 1 sequences
+ *   num_heads            must be MLA_NUM_HEADS
+ *   max_seqlen_kv        >= 1, rows allocated per sequence in the KV cache
+ *   num_workgroups       workgroups the KV stream is divided over; 0 = automatic
+ *   bytes                [out, host] workspace size the call needs
+ *   num_workgroups_used  [out, host, may be NULL] the number the size was computed for
  */
-mla_status_t mla_decode_workspace_size(int batch, int num_heads, int max_seqlen_kv, int num_cus,
-                                       size_t *bytes, int *chunk_len, int *num_splits_max);
+mla_status_t mla_decode_workspace_size(int batch, int num_heads, int max_seqlen_kv,
+                                       int num_workgroups, size_t *bytes,
+                                       int *num_workgroups_used);
 
 /*
  * One decode-attention call.
@@ -79,7 +83,7 @@ mla_status_t mla_decode_workspace_size(int batch, int num_heads, int max_seqlen_
  *   scale           multiplies q.k before the softmax (1/sqrt(192) for DeepSeek-R1)
  *   out             device, fp32 [batch][1][16][512], contiguous, 16-byte aligned
  *   lse             device, fp32 [batch][16]: natural log of sum_t exp(scale * q.k_t)
- *   workspace       device, 16-byte aligned, >= mla_decode_workspace_size() bytes;
+ *   workspace       device, 16-byte aligned, >= mla_decode_workspace_size(.., 0, ..) bytes;
  *                   contents on entry are irrelevant, contents on exit unspecified
  *   stream          hipStream_t (as void*), NULL = the default stream
  *
@@ -93,27 +97,25 @@ mla_status_t mla_decode(const void *q, const void *kv_cache, int64_t kv_batch_st
 
 /*
  * Extended call for tuning sweeps, tests of the log-sum-exp merge and per-kernel timing.
- *   chunk_len  0 = the automatic plan of mla_decode(); otherwise a positive multiple of
- *              MLA_CHUNK_GRANULE KV tokens per workgroup.  With a forced chunk the workspace
- *              must hold mla_decode_workspace_size_for_chunk() bytes.
- *   phases     MLA_PHASE_SPLIT launches the split-KV main kernel (every step of Algorithm 1
- *              on each chunk), MLA_PHASE_COMBINE launches the merge of the chunk results;
- *              mla_decode() is both.  Running the combine phase alone is only meaningful
- *              after a split phase with the same arguments and workspace.
+ *   num_workgroups  0 = the automatic plan of mla_decode(); otherwise the number of
+ *                   workgroups (1 .. 65536) the stream of MLA_UNIT_TOKENS-token units is
+ *                   divided over.  The workspace must hold the size
+ *                   mla_decode_workspace_size() returns for the same number.
+ *   flags           MLA_PHASE_SPLIT launches the split-KV main kernel (every step of
+ *                   Algorithm 1 on each workgroup's tiles), MLA_PHASE_COMBINE launches the
+ *                   merge of the workgroups' results; at least one of the two must be set and
+ *                   mla_decode() is both.  Running the combine phase alone is only meaningful
+ *                   after a split phase with the same arguments and workspace.
  * All other arguments, and all error behaviour, are those of mla_decode().
  */
-#define MLA_CHUNK_GRANULE 128
+#define MLA_UNIT_TOKENS 128
 #define MLA_PHASE_SPLIT 1
 #define MLA_PHASE_COMBINE 2
 mla_status_t mla_decode_ex(const void *q, const void *kv_cache, int64_t kv_batch_stride,
                            const int32_t *cache_seqlens, int batch, int num_heads,
                            int max_seqlen_kv, float scale, float *out, float *lse,
-                           void *workspace, size_t workspace_bytes, int chunk_len, int phases,
-                           void *stream);
-
-/* Workspace size for a forced chunk length (host only, no device access). */
-mla_status_t mla_decode_workspace_size_for_chunk(int batch, int max_seqlen_kv, int chunk_len,
-                                                 size_t *bytes, int *num_splits_max);
+                           void *workspace, size_t workspace_bytes, int num_workgroups,
+                           int flags, void *stream);
 
 /* Static string for a status code (never NULL). */
 const char *mla_status_string(mla_status_t status);

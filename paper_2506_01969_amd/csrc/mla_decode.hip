@@ -14,14 +14,23 @@
 // per-head softmax statistics and the per-head rescale factor of Algorithm 1 become per-lane
 // scalars.  The transpose of equation (4) is folded into the addressing of the final store.
 //
-// Work decomposition.  One workgroup (4 wavefronts) per (sequence, KV chunk).  Each wavefront is
-// an independent online-softmax worker (the m / l / rescale recurrence of Algorithm 1) over
-// every 4th 32-token tile of the chunk, with a private LDS tile, so the main loop has no
-// barrier.  A tile is fetched with 16-byte coalesced global loads into registers (in flight
-// while the previous tile is being computed), written once to LDS, and read twice from LDS: as
-// the K operand (ds_read_b128) and, through the transposing LDS read ds_read_b64_tr_b16, as the
-// V^T operand.  The four wavefronts merge their (m, l, O) through LDS at the end of the chunk;
-// chunks are merged by the combine kernel.
+// Work decomposition.  The KV rows of all sequences form one stream of 128-token units
+// (a sequence of N tokens holds ceil(N/128) units).  The grid is persistent: workgroup k of G
+// takes the contiguous unit range [k*U/G, (k+1)*U/G) of that stream, whatever the lengths are,
+// so ragged batches are balanced to one unit and every workgroup streams the same amount.
+// A range may cross sequence boundaries; each (workgroup, sequence) piece is a "segment" and ends
+// with its own epilogue.  Every workgroup derives the partition from cache_seqlens on the device
+// (one vector load and a wave scan), so the host never needs the lengths.  The assignment is
+// static: results are bit-identical from run to run.
+//
+// Each wavefront is an independent online-softmax worker (the m / l / rescale recurrence of
+// Algorithm 1) over every 4th 32-token tile of the segment, with a
+// private LDS tile, so the main loop has no barrier.  A tile is fetched with 16-byte coalesced
+// global loads into registers (in flight while the previous tile is being computed), written
+// once to LDS, and read twice from LDS: as the K operand (ds_read_b128) and, through the
+// transposing LDS read ds_read_b64_tr_b16, as the V^T operand.  The four wavefronts of a
+// workgroup merge their (m, l, O) through LDS at the end of the segment; a sequence
+// shared by several workgroups is finished by the combine kernel.
 //
 // P is fed to the second MFMA as a two-term bf16 split (hi + lo): a single bf16 rounding of P
 // costs ~2^-9 relative error per term, which is outside the 1e-4 RMSE bound at short KV.
@@ -45,14 +54,20 @@ constexpr int kTile = 32;                    // tokens per wavefront step (MFMA 
 constexpr int kWaves = 4;                    // wavefronts per workgroup
 constexpr int kThreads = kWaves * 64;
 constexpr int kWaveLds = kTile * kLdsRow;    // 37,376 B private tile per wavefront
+constexpr int kTileLoads = kTile * kRowBytes / 1024;   // 36 loads of 64 lanes x 16 B per tile
+static_assert(kTileLoads * 1024 == kTile * kRowBytes, "a tile must be a whole number of 1 KB pieces");
 constexpr int kKSteps = kDqk / 32;           // 18 MFMA k-steps over the 576 dims
 constexpr int kDvTiles = kDv / 16;           // 32 output tiles of 16 value columns
 constexpr int kStatsOff = kWaves * kWaveLds; // m and l of the 4 wavefronts live after the tiles
 constexpr int kRescaleOff = kStatsOff + 2 * kWaves * kHeads * 4;  // 2 KB per wavefront, cold rescale path
 constexpr int kLdsBytes = kRescaleOff + kWaves * 2048;
-constexpr int kChunkGranule = kWaves * kTile;  // 128: chunk lengths are multiples of this
-static_assert(kChunkGranule == MLA_CHUNK_GRANULE, "header and kernel disagree on the chunk granule");
+constexpr int kUnit = kWaves * kTile;          // 128 tokens: the scheduling unit (one tile per wavefront)
+static_assert(kUnit == MLA_UNIT_TOKENS, "header and kernel disagree on the scheduling unit");
 constexpr int kCombineThreads = 128;
+constexpr int kSchedMfma = 0x008;              // instruction classes of sched_group_barrier
+constexpr int kSchedDsRead = 0x100;
+constexpr int kKAhead = 4;                     // k-steps of K operand reads in flight ahead of the QK MFMAs
+constexpr int kVAhead = 6;                     // value tiles of V^T reads in flight ahead of the PV MFMAs
 
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
@@ -68,20 +83,90 @@ struct Params {
     const int *seqlens;       // [batch]
     float *out;               // [batch][16][512]
     float *lse;               // [batch][16]
-    float *part_out;          // [batch][splits_max][16][512]
-    float *part_lse;          // [batch][splits_max][16], base-2 log-sum-exp of scale*log2(e)*q.k
+    float *part_out;          // [num_wg + batch][16][512]: slot of (workgroup k, sequence b) is k + b
+    float *part_lse;          // [num_wg + batch][16], base-2 log-sum-exp of scale*log2(e)*q.k
+    int batch;
     int max_seqlen;
-    int chunk_len;
-    int splits_max;
+    int num_wg;               // G: workgroups the unit stream is divided over (= grid of the main kernel)
     float scale_log2e;        // scale * log2(e): scores are kept in the base-2 domain
 };
 
-__device__ __forceinline__ u32x4 load_stream16(const char *p) {
-    return __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(p));
+__device__ __forceinline__ int clamped_len(const Params &p, int b) {
+    const int n = p.seqlens[b];
+    return n < 0 ? 0 : (n > p.max_seqlen ? p.max_seqlen : n);
+}
+
+__device__ __forceinline__ int units_of(int n) { return (n + kUnit - 1) / kUnit; }
+
+__device__ __forceinline__ int wave_sum(int v) {
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, 64);
+    return v;
+}
+
+// Units of all sequences (total) and of the sequences before b, one sequence per lane and 64 at
+// a time, so the lengths are fetched with one vector load instead of a chain of dependent scalar
+// loads.  Every wavefront computes this for itself; the results are wave-uniform.
+__device__ __forceinline__ void unit_sums(const Params &p, int lane, int b, int &total, int &before_b) {
+    int tot = 0, bef = 0;
+    for (int base = 0; base < p.batch; base += 64) {
+        const int i = base + lane;
+        const int u = i < p.batch ? units_of(clamped_len(p, i)) : 0;
+        tot += u;
+        bef += i < b ? u : 0;
+    }
+    total = __builtin_amdgcn_readfirstlane(wave_sum(tot));
+    before_b = __builtin_amdgcn_readfirstlane(wave_sum(bef));
+}
+
+// The sequence that holds unit `target` of the stream (0 <= target < total units) and the stream
+// index of that sequence's first unit: b = number of sequences whose inclusive prefix is <= target.
+__device__ __forceinline__ void locate_unit(const Params &p, int lane, int target, int &b, int &first) {
+    int carry = 0, count = 0, start = 0;
+    for (int base = 0; base < p.batch; base += 64) {
+        const int i = base + lane;
+        int incl = i < p.batch ? units_of(clamped_len(p, i)) : 0;
+#pragma unroll
+        for (int d = 1; d < 64; d <<= 1) {              // inclusive scan across the wavefront
+            const int up = __shfl_up(incl, d, 64);
+            if (lane >= d) incl += up;
+        }
+        incl += carry;
+        const unsigned long long below = __builtin_amdgcn_ballot_w64(i < p.batch && incl <= target);
+        if (below != 0) {
+            count += __builtin_popcountll(below);
+            start = __builtin_amdgcn_readlane(incl, 63 - __builtin_clzll(below));
+        }
+        carry = __builtin_amdgcn_readlane(incl, 63);
+    }
+    b = count;
+    first = start;
+}
+
+// 16-byte streaming load at (wave-uniform base) + (32-bit lane offset): the uniform part stays in
+// scalar registers and the lane part is one VGPR, so a tile's 36 loads cost no address arithmetic.
+__device__ __forceinline__ u32x4 load_stream16(const char *uniform_base, unsigned lane_off) {
+    return __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(uniform_base + lane_off));
+}
+
+// Transposing LDS read of a 4 (rows) x 16 (columns) block of 16-bit elements per 16-lane group.
+__device__ __forceinline__ i16x4 read_tr16(const char *lds_addr) {
+    return __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+        (__attribute__((address_space(3))) i16x4 *)(lds_char *)lds_addr);
 }
 
 __device__ __forceinline__ float wave_xor_max(float v, int mask) {
     return fmaxf(v, __shfl_xor(v, mask, 64));
+}
+
+// Workgroups bound to the sequence that owns stream units [seq_first, seq_first + ub): workgroup k
+// is bound iff its share [floor(k U / G), floor((k+1) U / G)) meets that range, which gives
+//   first = ceil((seq_first + 1) G / U) - 1,   last = ceil((seq_first + ub) G / U) - 1.
+__device__ __forceinline__ void bound_workgroups(int seq_first, int ub, int total_units, int active,
+                                                 int &first, int &last) {
+    const long long U = total_units, G = active;
+    first = (int)((((long long)seq_first + 1) * G + U - 1) / U) - 1;
+    last = (int)((((long long)seq_first + ub) * G + U - 1) / U) - 1;
 }
 
 constexpr float kLazyLog2 = 8.0f;   // the softmax reference moves only when exceeded by 2^8
@@ -103,7 +188,8 @@ __device__ __forceinline__ void rescale_accumulators(f32x4 (&o)[kDvTiles], float
     }
 }
 
-// Main kernel: one workgroup per (sequence, chunk); steps a1-a7 of the hot path.
+// Main kernel (steps a0-a7 of the hot path): persistent grid, workgroup k streams its share of
+// the unit stream segment by segment.
 __global__ void __launch_bounds__(kThreads, 1) mla_decode_split_kernel(const Params p) {
     extern __shared__ __attribute__((aligned(16))) char smem[];
 
@@ -113,214 +199,313 @@ __global__ void __launch_bounds__(kThreads, 1) mla_decode_split_kernel(const Par
     const int r16 = l & 15;       // MFMA row/column index owned by this lane
     const int g = l >> 4;         // MFMA k-group (0..3)
 
-    const int b = blockIdx.x / p.splits_max;
-    const int s = blockIdx.x - b * p.splits_max;
-    int n = p.seqlens[b];
-    n = n < 0 ? 0 : (n > p.max_seqlen ? p.max_seqlen : n);
-    const int t_begin = s * p.chunk_len;
-    if (t_begin >= n) return;     // chunk past the end of this sequence (uniform over the workgroup)
-    const int t_end = min(n, t_begin + p.chunk_len);
-    const int num_splits = (n + p.chunk_len - 1) / p.chunk_len;
-    const int n_tiles = (t_end - t_begin + kTile - 1) / kTile;
-    const char *kv_b = p.kv + (long long)b * p.kv_batch_bytes;
-
-    // Q^T as the MFMA B operand: lane (head r16, k-group g) holds dims 32*kk + 8*g .. +8.
-    bf16x8 qf[kKSteps];
-    {
-        const u32x4 *qp = reinterpret_cast<const u32x4 *>(p.q + ((long long)b * kHeads + r16) * kRowBytes) + g;
-#pragma unroll
-        for (int kk = 0; kk < kKSteps; ++kk) qf[kk] = __builtin_bit_cast(bf16x8, qp[4 * kk]);
-    }
+    // ---- a0 on the device: this workgroup's range of the unit stream -------------------------
+    const int k = blockIdx.x;
+    int total_units, unused;
+    unit_sums(p, l, 0, total_units, unused);
+    // never more workgroups than units: every active workgroup then holds at least one unit
+    const int active = total_units < p.num_wg ? total_units : p.num_wg;
+    if (k >= active) return;                        // uniform over the workgroup
+    const int u_lo = (int)((long long)k * total_units / active);
+    const int u_hi = (int)((long long)(k + 1) * total_units / active);   // > u_lo
+    int b, seq_first;                               // first sequence of the range, stream index of its first unit
+    locate_unit(p, l, u_lo, b, seq_first);
 
     char *my = smem + w * kWaveLds;                       // private tile of this wavefront
     // LDS addresses (bytes) of the three access patterns
-    char *wr_main = my + l * 16;                          // row i, 16-byte chunk l            (+ i*kLdsRow)
-    char *wr_rest = my + (l >> 3) * kLdsRow + 1024 + (l & 7) * 16;  // rows 8j + l/8, chunk 64 + l%8 (+ j*8*kLdsRow)
+    // write side: piece i, lane l holds chunk 64 i + l; lanes at or past the row boundary inside
+    // the piece (lane 72 (q+1) - 64 i, a function of i mod 9) skip the 16-byte row padding
+    char *wr_flat[9];
+#pragma unroll
+    for (int r = 0; r < 9; ++r) {
+        const int boundary = 72 * ((r * 64) / 72 + 1) - r * 64;     // 72, 8, 16, ..., 56, 64
+        wr_flat[r] = my + l * 16 + (l >= boundary ? 16 : 0);
+    }
     const char *rd_k = my + r16 * kLdsRow + g * 16;       // K operand: token r16 (+16), chunk 4*kk + g
     // V^T operand through the transposing read: within each 16-lane group, lane j points at
     // row j/4, columns 4*(j%4)..+3 of a 4x16 block and receives column j, rows 0..3.
     const char *rd_v = my + (4 * g + (r16 >> 2)) * kLdsRow + (r16 & 3) * 8;
-
-    f32x4 o[kDvTiles];
-#pragma unroll
-    for (int ct = 0; ct < kDvTiles; ++ct) o[ct] = f32x4{0.f, 0.f, 0.f, 0.f};
-    float m_run = -INFINITY;      // running maximum of this lane's head (base-2 domain)
-    float l_run = 0.f;            // this lane's share of the running sum
-
-    u32x4 st[kTile + 4];          // one tile in flight: 36 x 16 B per lane
-
-    // Rows past the end of the sequence are never fetched: their addresses are clamped to the
-    // last valid row (their scores are masked below, so the duplicate has weight zero).
-    auto issue_loads = [&](int tile) {
-        const int tb = t_begin + tile * kTile;
-#pragma unroll
-        for (int i = 0; i < kTile; ++i) {
-            const int row = min(tb + i, n - 1);
-            st[i] = load_stream16(kv_b + (long long)row * kRowBytes + l * 16);
-        }
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            const int row = min(tb + 8 * j + (l >> 3), n - 1);
-            st[kTile + j] = load_stream16(kv_b + (long long)row * kRowBytes + 1024 + (l & 7) * 16);
-        }
-    };
-
-    if (w < n_tiles) issue_loads(w);
-
-    for (int tile = w; tile < n_tiles; tile += kWaves) {
-        const int tb = t_begin + tile * kTile;
-
-        // ---- a2: registers -> private LDS tile --------------------------------------------
-#pragma unroll
-        for (int i = 0; i < kTile; ++i) *reinterpret_cast<u32x4 *>(wr_main + i * kLdsRow) = st[i];
-#pragma unroll
-        for (int j = 0; j < 4; ++j) *reinterpret_cast<u32x4 *>(wr_rest + j * 8 * kLdsRow) = st[kTile + j];
-
-        // next tile of this wavefront goes in flight now and lands while this one is computed
-        if (tile + kWaves < n_tiles) issue_loads(tile + kWaves);
-
-        // ---- a3: S^T = K Q^T for tokens 0..15 and 16..31 of the tile (equation (1)) ------
-        f32x4 s0 = {0.f, 0.f, 0.f, 0.f}, s1 = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-        for (int kk = 0; kk < kKSteps; ++kk) {
-            const bf16x8 k0 = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4 *>(rd_k + kk * 64));
-            const bf16x8 k1 = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4 *>(rd_k + 16 * kLdsRow + kk * 64));
-            s0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(k0, qf[kk], s0, 0, 0, 0);
-            s1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(k1, qf[kk], s1, 0, 0, 0);
-        }
-        // this lane now holds, for head r16, tokens tb + 4g + i (s0[i]) and tb + 16 + 4g + i (s1[i])
-
-        // ---- a4: scale (base-2 domain) and mask the tail ----------------------------------
-        float x[8];
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            x[i] = (tb + 4 * g + i < t_end) ? s0[i] * p.scale_log2e : -INFINITY;
-            x[4 + i] = (tb + 16 + 4 * g + i < t_end) ? s1[i] * p.scale_log2e : -INFINITY;
-        }
-
-        // ---- a5: online softmax (Algorithm 1: m, l update) ---------------------------------
-        // The reference maximum m_run moves lazily: exponentials are taken against the current
-        // reference and O, l are rescaled by exp(m_old - m_new) (the R of Algorithm 1) only when
-        // some head's tile maximum exceeds its reference by more than kLazyLog2 (so p <= 2^8).
-        // Any reference gives the same O / l and m + log l; moving it rarely keeps the 128
-        // accumulator registers out of the vector ALU on almost every tile.
-        float mx = fmaxf(fmaxf(fmaxf(x[0], x[1]), fmaxf(x[2], x[3])), fmaxf(fmaxf(x[4], x[5]), fmaxf(x[6], x[7])));
-        mx = wave_xor_max(mx, 16);
-        mx = wave_xor_max(mx, 32);                       // finite: every tile has >= 1 valid token
-        if (tile == w) {
-            m_run = mx;                                  // first tile: O = 0 and l = 0, nothing to rescale
-        } else if (__builtin_amdgcn_ballot_w64(mx > m_run + kLazyLog2) != 0) {
-            const float m_new = fmaxf(m_run, mx);
-            const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
-            rescale_accumulators(o, alpha, smem + kRescaleOff + w * 2048 + l * 16);
-            l_run *= alpha;
-            m_run = m_new;
-        }
-        float pr[8];
-#pragma unroll
-        for (int i = 0; i < 8; ++i) {
-            pr[i] = __builtin_amdgcn_exp2f(x[i] - m_run);
-            l_run += pr[i];
-        }
-
-        // P^T as B operand, two-term bf16 split
-        bf16x8 p_hi, p_lo;
-#pragma unroll
-        for (int i = 0; i < 8; ++i) {
-            p_hi[i] = (__bf16)pr[i];
-            p_lo[i] = (__bf16)(pr[i] - (float)p_hi[i]);
-        }
-
-        // ---- a6: O^T += V^T P^T (equation (3)), V^T from the same LDS tile ------------------
-#pragma unroll
-        for (int ct = 0; ct < kDvTiles; ++ct) {
-            const i16x4 v0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-                (__attribute__((address_space(3))) i16x4 *)(lds_char *)(rd_v + ct * 32));
-            const i16x4 v1 = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-                (__attribute__((address_space(3))) i16x4 *)(lds_char *)(rd_v + 16 * kLdsRow + ct * 32));
-            const i16x4 vv[2] = {v0, v1};
-            bf16x8 vt;
-            __builtin_memcpy(&vt, vv, 16);
-            o[ct] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vt, p_hi, o[ct], 0, 0, 0);
-            o[ct] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vt, p_lo, o[ct], 0, 0, 0);
-        }
-    }
-
-    // ---- a7: merge the four wavefronts, normalise, write (the epilogue of Algorithm 1) --------
-    l_run += __shfl_xor(l_run, 16, 64);
-    l_run += __shfl_xor(l_run, 32, 64);
     float *stat_m = reinterpret_cast<float *>(smem + kStatsOff);
     float *stat_l = stat_m + kWaves * kHeads;
-    if (g == 0) {
-        stat_m[w * kHeads + r16] = m_run;
-        stat_l[w * kHeads + r16] = l_run;
-    }
-    // own accumulators into the own (now idle) tile: [ct][lane] x 16 B
-#pragma unroll
-    for (int ct = 0; ct < kDvTiles; ++ct) *reinterpret_cast<f32x4 *>(my + ct * 1024 + l * 16) = o[ct];
-    __syncthreads();
+    const unsigned lane16 = (unsigned)l * 16;               // global-load lane offsets (bytes)
 
-    float m_tot = stat_m[r16];
-#pragma unroll
-    for (int ww = 1; ww < kWaves; ++ww) m_tot = fmaxf(m_tot, stat_m[ww * kHeads + r16]);
-    float f[kWaves];
-    float l_tot = 0.f;
-#pragma unroll
-    for (int ww = 0; ww < kWaves; ++ww) {
-        f[ww] = __builtin_amdgcn_exp2f(stat_m[ww * kHeads + r16] - m_tot);   // 0 for an idle wavefront
-        l_tot += f[ww] * stat_l[ww * kHeads + r16];
-    }
-    const float inv_l = 1.0f / l_tot;
-#pragma unroll
-    for (int ww = 0; ww < kWaves; ++ww) f[ww] *= inv_l;
+    int cur_unit = u_lo;
+    while (cur_unit < u_hi) {
+        const int n = clamped_len(p, b);
+        const int ub = units_of(n);                            // > 0
+        const int u_begin = cur_unit - seq_first;
+        const int u_end = min(u_hi - seq_first, ub);           // > u_begin
+        const int t_begin = u_begin * kUnit;
+        const int t_end = min(n, u_end * kUnit);
+        const int n_tiles = (t_end - t_begin + kTile - 1) / kTile;
+        const bool direct = (u_begin == 0 && u_end == ub);     // this workgroup covers the whole sequence
+        const char *kv_b = p.kv + (long long)b * p.kv_batch_bytes;
 
-    const bool direct = (num_splits == 1);
-    float *dst = direct ? p.out + ((long long)b * kHeads + r16) * kDv
-                        : p.part_out + (((long long)b * p.splits_max + s) * kHeads + r16) * kDv;
-    // wavefront w finishes value tiles 8w .. 8w+7; lane holds head r16, columns 16ct + 4g .. +3
+        u32x4 st[kTileLoads];         // one tile in flight: 36 x 16 B per lane
+
+        // A tile is 32 consecutive rows = 36,864 contiguous bytes, fetched as 36 pieces of 1 KB
+        // (lane l of piece i reads 16-byte chunk 64 i + l).  Fully sequential 1 KB requests
+        // stream measurably faster from HBM than row-shaped ones.  Rows past the end of the
+        // sequence are never fetched: chunk indices are clamped to the last valid chunk (the
+        // scores of those rows are masked below, so whatever lands there has weight zero and
+        // is finite data of a valid row).
+        auto issue_loads = [&](int tile) {
+            const int tb = t_begin + tile * kTile;
+            const int valid_rows = min(n - tb, kTile);                 // >= 1
+            const int last_chunk16 = (valid_rows * (kRowBytes / 16) - 1) * 16;   // byte offset of the last valid chunk
+            const char *tile_base = kv_b + (long long)tb * kRowBytes;
 #pragma unroll
-    for (int c = 0; c < kDvTiles / kWaves; ++c) {
-        const int ct = w * (kDvTiles / kWaves) + c;
-        f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+            for (int i = 0; i < kTileLoads; ++i) {
+                const int piece = min(i * 1024, last_chunk16);          // scalar
+                st[i] = load_stream16(tile_base + piece, min(lane16, (unsigned)(last_chunk16 - piece)));
+            }
+        };
+        // ---- a1: Q^T as the MFMA B operand: lane (head r16, k-group g) holds dims 32*kk + 8*g .. +8
+        bf16x8 qf[kKSteps];
+        {
+            const u32x4 *qp = reinterpret_cast<const u32x4 *>(p.q + ((long long)b * kHeads + r16) * kRowBytes) + g;
+#pragma unroll
+            for (int kk = 0; kk < kKSteps; ++kk) qf[kk] = __builtin_bit_cast(bf16x8, qp[4 * kk]);
+        }
+
+        // this wavefront's tiles of the segment: w, w + 4, w + 8, ...
+        int cur = w, nxt = w + kWaves;
+        if (cur < n_tiles) issue_loads(cur);
+
+        // Q must be resident before the tile loop.  It was requested ahead of the first tile, so
+        // this waits for Q alone; left to the loop, the wait for Q would be re-evaluated on every
+        // tile with a count that also drains the prefetch of the next tile.
+#pragma unroll
+        for (int kk = 0; kk < kKSteps; ++kk) asm volatile("" : "+v"(qf[kk]));
+
+        f32x4 o[kDvTiles];
+#pragma unroll
+        for (int ct = 0; ct < kDvTiles; ++ct) o[ct] = f32x4{0.f, 0.f, 0.f, 0.f};
+        float m_run = -INFINITY;      // softmax reference of this lane's head (base-2 domain)
+        float l_run = 0.f;            // this lane's share of the running sum
+
+        bool first_tile = true;
+        while (cur < n_tiles) {
+            const int tb = t_begin + cur * kTile;
+
+            // ---- a2: registers -> private LDS tile ----------------------------------------
+            // chunk c = 64 i + l goes to row c / 72, column chunk c % 72: byte 16 (c + c / 72)
+#pragma unroll
+            for (int i = 0; i < kTileLoads; ++i)
+                *reinterpret_cast<u32x4 *>(wr_flat[i % 9] + i * 1024 + ((i * 64) / 72) * 16) = st[i];
+
+            // the next tile of this wavefront goes in flight now and lands while this one is computed
+            if (nxt < n_tiles) issue_loads(nxt);
+
+            // ---- a3: S^T = K Q^T for tokens 0..15 and 16..31 of the tile (equation (1)) --
+            // LDS reads run kKAhead k-steps ahead of the MFMAs that consume them.
+            f32x4 s0 = {0.f, 0.f, 0.f, 0.f}, s1 = {0.f, 0.f, 0.f, 0.f};
+            {
+                u32x4 kb[kKAhead][2];
+#pragma unroll
+                for (int kk = 0; kk < kKAhead; ++kk) {
+                    kb[kk][0] = *reinterpret_cast<const u32x4 *>(rd_k + kk * 64);
+                    kb[kk][1] = *reinterpret_cast<const u32x4 *>(rd_k + 16 * kLdsRow + kk * 64);
+                }
+#pragma unroll
+                for (int kk = 0; kk < kKSteps; ++kk) {
+                    const bf16x8 k0 = __builtin_bit_cast(bf16x8, kb[kk % kKAhead][0]);
+                    const bf16x8 k1 = __builtin_bit_cast(bf16x8, kb[kk % kKAhead][1]);
+                    if (kk + kKAhead < kKSteps) {
+                        kb[kk % kKAhead][0] = *reinterpret_cast<const u32x4 *>(rd_k + (kk + kKAhead) * 64);
+                        kb[kk % kKAhead][1] = *reinterpret_cast<const u32x4 *>(rd_k + 16 * kLdsRow + (kk + kKAhead) * 64);
+                    }
+                    s0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(k0, qf[kk], s0, 0, 0, 0);
+                    s1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(k1, qf[kk], s1, 0, 0, 0);
+                }
+                // pin that interleaving for the instruction scheduler: reads first, then
+                // (2 MFMA, 2 LDS reads) per k-step, so LDS latency hides behind the MFMAs
+                __builtin_amdgcn_sched_group_barrier(kSchedDsRead, 2 * kKAhead, 0);
+#pragma unroll
+                for (int kk = 0; kk < kKSteps; ++kk) {
+                    __builtin_amdgcn_sched_group_barrier(kSchedMfma, 2, 0);
+                    if (kk + kKAhead < kKSteps) __builtin_amdgcn_sched_group_barrier(kSchedDsRead, 2, 0);
+                }
+            }
+            // this lane now holds, for head r16, tokens tb + 4g + i (s0[i]) and tb + 16 + 4g + i (s1[i])
+
+            // ---- a4: scale (base-2 domain) and mask the tail ------------------------------
+            float x[8];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                x[i] = (tb + 4 * g + i < t_end) ? s0[i] * p.scale_log2e : -INFINITY;
+                x[4 + i] = (tb + 16 + 4 * g + i < t_end) ? s1[i] * p.scale_log2e : -INFINITY;
+            }
+
+            // ---- a5: online softmax (Algorithm 1: m, l update) -----------------------------
+            // The reference maximum m_run moves lazily: exponentials are taken against the
+            // current reference and O, l are rescaled by exp(m_old - m_new) (the R of Algorithm
+            // 1) only when some head's tile maximum exceeds its reference by more than
+            // kLazyLog2 (so p <= 2^8).  Any reference gives the same O / l and m + log l; moving
+            // it rarely keeps the 128 accumulator registers out of the vector ALU on almost
+            // every tile.
+            float mx = fmaxf(fmaxf(fmaxf(x[0], x[1]), fmaxf(x[2], x[3])), fmaxf(fmaxf(x[4], x[5]), fmaxf(x[6], x[7])));
+            mx = wave_xor_max(mx, 16);
+            mx = wave_xor_max(mx, 32);                       // finite: every tile has >= 1 valid token
+            if (first_tile) {
+                m_run = mx;                                  // first tile: O = 0 and l = 0, nothing to rescale
+                first_tile = false;
+            } else if (__builtin_amdgcn_ballot_w64(mx > m_run + kLazyLog2) != 0) {
+                const float m_new = fmaxf(m_run, mx);
+                const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
+                rescale_accumulators(o, alpha, smem + kRescaleOff + w * 2048 + l * 16);
+                l_run *= alpha;
+                m_run = m_new;
+            }
+            float pr[8];
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                pr[i] = __builtin_amdgcn_exp2f(x[i] - m_run);
+                l_run += pr[i];
+            }
+
+            // P^T as B operand, two-term bf16 split
+            bf16x8 p_hi, p_lo;
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                p_hi[i] = (__bf16)pr[i];
+                p_lo[i] = (__bf16)(pr[i] - (float)p_hi[i]);
+            }
+
+            // ---- a6: O^T += V^T P^T (equation (3)), V^T from the same LDS tile --------------
+            // The transposing reads run kVAhead value tiles ahead of their MFMAs.
+            {
+                i16x4 vb[kVAhead][2];
+#pragma unroll
+                for (int ct = 0; ct < kVAhead; ++ct) {
+                    vb[ct][0] = read_tr16(rd_v + ct * 32);
+                    vb[ct][1] = read_tr16(rd_v + 16 * kLdsRow + ct * 32);
+                }
+#pragma unroll
+                for (int ct = 0; ct < kDvTiles; ++ct) {
+                    const i16x4 vv[2] = {vb[ct % kVAhead][0], vb[ct % kVAhead][1]};
+                    bf16x8 vt;
+                    __builtin_memcpy(&vt, vv, 16);
+                    if (ct + kVAhead < kDvTiles) {
+                        vb[ct % kVAhead][0] = read_tr16(rd_v + (ct + kVAhead) * 32);
+                        vb[ct % kVAhead][1] = read_tr16(rd_v + 16 * kLdsRow + (ct + kVAhead) * 32);
+                    }
+                    o[ct] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vt, p_hi, o[ct], 0, 0, 0);
+                    o[ct] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vt, p_lo, o[ct], 0, 0, 0);
+                }
+                __builtin_amdgcn_sched_group_barrier(kSchedDsRead, 2 * kVAhead, 1);
+#pragma unroll
+                for (int ct = 0; ct < kDvTiles; ++ct) {
+                    __builtin_amdgcn_sched_group_barrier(kSchedMfma, 2, 1);
+                    if (ct + kVAhead < kDvTiles) __builtin_amdgcn_sched_group_barrier(kSchedDsRead, 2, 1);
+                }
+            }
+
+            cur = nxt;
+            nxt += kWaves;
+        }
+
+        // ---- a7: merge the four wavefronts, normalise, write (the epilogue of Algorithm 1) ----
+        l_run += __shfl_xor(l_run, 16, 64);
+        l_run += __shfl_xor(l_run, 32, 64);
+        if (g == 0) {
+            stat_m[w * kHeads + r16] = m_run;
+            stat_l[w * kHeads + r16] = l_run;
+        }
+        // own accumulators into the own (now idle) tile: [ct][lane] x 16 B
+#pragma unroll
+        for (int ct = 0; ct < kDvTiles; ++ct) *reinterpret_cast<f32x4 *>(my + ct * 1024 + l * 16) = o[ct];
+        __syncthreads();
+
+        float m_tot = stat_m[r16];
+#pragma unroll
+        for (int ww = 1; ww < kWaves; ++ww) m_tot = fmaxf(m_tot, stat_m[ww * kHeads + r16]);
+        const bool none = (m_tot == -INFINITY);      // the whole workgroup drew no tile of this sequence
+        float f[kWaves];
+        float l_tot = 0.f;
 #pragma unroll
         for (int ww = 0; ww < kWaves; ++ww) {
-            const f32x4 part = *reinterpret_cast<const f32x4 *>(smem + ww * kWaveLds + ct * 1024 + l * 16);
-            acc += part * f[ww];
+            f[ww] = none ? 0.f : __builtin_amdgcn_exp2f(stat_m[ww * kHeads + r16] - m_tot);   // 0 for an idle wavefront
+            l_tot += f[ww] * stat_l[ww * kHeads + r16];
         }
-        *reinterpret_cast<f32x4 *>(dst + ct * 16 + g * 4) = acc;   // equation (4): transpose by addressing
-    }
-    if (w == 0 && g == 0) {
-        const float lse2 = m_tot + __builtin_amdgcn_logf(l_tot);   // v_log_f32 is log2
-        if (direct) p.lse[b * kHeads + r16] = lse2 * 0.6931471805599453f;
-        else p.part_lse[((long long)b * p.splits_max + s) * kHeads + r16] = lse2;
+        const float inv_l = none ? 0.f : 1.0f / l_tot;
+#pragma unroll
+        for (int ww = 0; ww < kWaves; ++ww) f[ww] *= inv_l;
+
+        const long long slot = (long long)k + b;
+        float *dst = direct ? p.out + ((long long)b * kHeads + r16) * kDv
+                            : p.part_out + (slot * kHeads + r16) * kDv;
+        // wavefront w finishes value tiles 8w .. 8w+7; lane holds head r16, columns 16ct + 4g .. +3
+#pragma unroll
+        for (int c = 0; c < kDvTiles / kWaves; ++c) {
+            const int ct = w * (kDvTiles / kWaves) + c;
+            f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int ww = 0; ww < kWaves; ++ww) {
+                const f32x4 part = *reinterpret_cast<const f32x4 *>(smem + ww * kWaveLds + ct * 1024 + l * 16);
+                acc += part * f[ww];
+            }
+            *reinterpret_cast<f32x4 *>(dst + ct * 16 + g * 4) = acc;   // equation (4): transpose by addressing
+        }
+        if (w == 0 && g == 0) {
+            const float lse2 = none ? -INFINITY : m_tot + __builtin_amdgcn_logf(l_tot);   // v_log_f32 is log2
+            if (direct) p.lse[b * kHeads + r16] = lse2 * 0.6931471805599453f;
+            else p.part_lse[slot * kHeads + r16] = lse2;
+        }
+
+        // next sequence this workgroup is bound to: the following one with at least one unit
+        cur_unit = seq_first + ub;
+        if (cur_unit < u_hi) {
+            __syncthreads();          // the tiles are overwritten next; everyone must be done reading them
+            seq_first += ub;
+            ++b;
+            while (units_of(clamped_len(p, b)) == 0) ++b;   // empty sequences hold no units
+        }
     }
 }
 
-// Combine kernel (step a8): per (sequence, head), merge the chunk partials by log-sum-exp.
-// The same m / l recurrence as Algorithm 1, applied across chunks instead of KV blocks.
+// Combine kernel (step a8): per (sequence, head), merge the partial results of the workgroups
+// that shared the sequence by log-sum-exp: the m / l recurrence of Algorithm 1 applied across
+// workgroups instead of KV blocks.  The set of workgroups follows from the same partition.
 __global__ void __launch_bounds__(kCombineThreads) mla_decode_combine_kernel(const Params p) {
     const int b = blockIdx.x / kHeads;
     const int h = blockIdx.x - b * kHeads;
     const int t = threadIdx.x;                // 128 threads x 4 columns
-    int n = p.seqlens[b];
-    n = n < 0 ? 0 : (n > p.max_seqlen ? p.max_seqlen : n);
-    const int ns = (n + p.chunk_len - 1) / p.chunk_len;
-    if (ns == 1) return;                      // the main kernel wrote out / lse directly
+    int total_units, seq_first;
+    unit_sums(p, t & 63, b, total_units, seq_first);
+    const int ub = units_of(clamped_len(p, b));
     float *out = p.out + ((long long)b * kHeads + h) * kDv + t * 4;
-    if (ns == 0) {                            // empty sequence
+    if (ub == 0) {                            // empty sequence
         *reinterpret_cast<f32x4 *>(out) = f32x4{0.f, 0.f, 0.f, 0.f};
         if (t == 0) p.lse[b * kHeads + h] = -INFINITY;
         return;
     }
-    const float *pl = p.part_lse + (long long)b * p.splits_max * kHeads + h;
+    const int active = total_units < p.num_wg ? total_units : p.num_wg;    // as in the main kernel
+    int k_first, k_last;
+    bound_workgroups(seq_first, ub, total_units, active, k_first, k_last);
+    const int ns = k_last - k_first + 1;
+    if (ns == 1) return;                      // the main kernel wrote out / lse directly
+    const float *pl = p.part_lse + ((long long)k_first + b) * kHeads + h;
     float m = -INFINITY;
     for (int s = 0; s < ns; ++s) m = fmaxf(m, pl[s * kHeads]);
     float sum = 0.f;
     for (int s = 0; s < ns; ++s) sum += __builtin_amdgcn_exp2f(pl[s * kHeads] - m);
     const float tot = m + __builtin_amdgcn_logf(sum);
-    const float *po = p.part_out + ((long long)b * p.splits_max * kHeads + h) * kDv + t * 4;
+    const float *po = p.part_out + (((long long)k_first + b) * kHeads + h) * kDv + t * 4;
     f32x4 acc = {0.f, 0.f, 0.f, 0.f};
-    for (int s = 0; s < ns; ++s) {
+    int s = 0;
+    for (; s + 8 <= ns; s += 8) {             // eight independent loads in flight per thread
+        f32x4 v[8];
+        float wgt[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            v[j] = *reinterpret_cast<const f32x4 *>(po + (long long)(s + j) * kHeads * kDv);
+            wgt[j] = __builtin_amdgcn_exp2f(pl[(s + j) * kHeads] - tot);
+        }
+#pragma unroll
+        for (int j = 0; j < 8; ++j) acc += v[j] * wgt[j];
+    }
+    for (; s < ns; ++s) {
         const float wgt = __builtin_amdgcn_exp2f(pl[s * kHeads] - tot);
         acc += *reinterpret_cast<const f32x4 *>(po + (long long)s * kHeads * kDv) * wgt;
     }
@@ -330,37 +515,24 @@ __global__ void __launch_bounds__(kCombineThreads) mla_decode_combine_kernel(con
 
 // ---- host side ---------------------------------------------------------------------------------
 
-inline size_t workspace_bytes_for(int batch, int splits_max) {
-    // partial outputs + partial LSEs, each part 16-byte aligned
-    const size_t po = (size_t)batch * splits_max * kHeads * kDv * sizeof(float);
-    const size_t pl = (size_t)batch * splits_max * kHeads * sizeof(float);
+inline size_t workspace_bytes_for(int batch, int num_wg) {
+    // one partial slot per (workgroup, sequence) pair that can occur: slot = k + b < num_wg + batch
+    const size_t slots = (size_t)num_wg + (size_t)batch;
+    const size_t po = slots * kHeads * kDv * sizeof(float);
+    const size_t pl = slots * kHeads * sizeof(float);
     return po + ((pl + 15) & ~(size_t)15);
 }
 
-// Split plan (step a0): tokens per workgroup so that batch * splits covers every compute unit
-// about `kUnitsPerCu` times; one workgroup is resident per compute unit.
-constexpr int kUnitsPerCu = 2;
-constexpr int kMinChunk = 256;
-
-int plan_chunk_len(int batch, int max_seqlen_kv, int num_cus) {
-    const long long total = (long long)batch * max_seqlen_kv;
-    const long long units = (long long)num_cus * kUnitsPerCu;
-    long long chunk = (total + units - 1) / units;
-    if (chunk < kMinChunk) chunk = kMinChunk;
-    chunk = (chunk + kChunkGranule - 1) / kChunkGranule * kChunkGranule;
-    // even out the chunks of one sequence: same number of splits, smallest chunk that covers it
-    const long long splits = (max_seqlen_kv + chunk - 1) / chunk;
-    chunk = (max_seqlen_kv + splits - 1) / splits;
-    chunk = (chunk + kChunkGranule - 1) / kChunkGranule * kChunkGranule;
-    return (int)chunk;
-}
+constexpr int kMaxWorkgroups = 1 << 16;
 
 bool misaligned(const void *ptr) { return (reinterpret_cast<uintptr_t>(ptr) & 15u) != 0; }
 
 mla_status_t check_shape(int batch, int num_heads, int max_seqlen_kv) {
     if (batch <= 0 || max_seqlen_kv <= 0 || num_heads <= 0) return MLA_ERR_INVALID_ARG;
     if (num_heads != kHeads) return MLA_ERR_UNSUPPORTED_SHAPE;
-    if ((long long)batch * max_seqlen_kv > (1ll << 40)) return MLA_ERR_INVALID_ARG;
+    // unit counts are summed in 32-bit integers on the device (a 288 GB cache holds < 2^28 tokens)
+    if ((long long)batch * max_seqlen_kv > (1ll << 30)) return MLA_ERR_INVALID_ARG;
+    if (batch > (1 << 20)) return MLA_ERR_INVALID_ARG;
     return MLA_OK;
 }
 
@@ -381,12 +553,10 @@ mla_status_t validate(const void *q, const void *kv_cache, int64_t kv_batch_stri
 // Everything below runs only after validate() passed.
 mla_status_t launch(const void *q, const void *kv_cache, int64_t kv_batch_stride,
                     const int32_t *cache_seqlens, int batch, int max_seqlen_kv, float scale,
-                    float *out, float *lse, void *workspace, size_t workspace_bytes, int chunk_len,
-                    int phases, void *stream) {
-    if (chunk_len <= 0 || chunk_len % kChunkGranule != 0) return MLA_ERR_INVALID_ARG;
-    const int splits_max = (max_seqlen_kv + chunk_len - 1) / chunk_len;
-    if ((long long)batch * splits_max > 0x7fffffffll) return MLA_ERR_INVALID_ARG;
-    if (workspace_bytes < workspace_bytes_for(batch, splits_max)) return MLA_ERR_WORKSPACE_TOO_SMALL;
+                    float *out, float *lse, void *workspace, size_t workspace_bytes, int num_wg,
+                    int flags, void *stream) {
+    if (num_wg <= 0 || num_wg > kMaxWorkgroups) return MLA_ERR_INVALID_ARG;
+    if (workspace_bytes < workspace_bytes_for(batch, num_wg)) return MLA_ERR_WORKSPACE_TOO_SMALL;
 
     // the main kernel needs more dynamic LDS than the default limit: raise it once per device
     static std::mutex mu;
@@ -411,18 +581,18 @@ mla_status_t launch(const void *q, const void *kv_cache, int64_t kv_batch_stride
     p.out = out;
     p.lse = lse;
     p.part_out = static_cast<float *>(workspace);
-    p.part_lse = p.part_out + (size_t)batch * splits_max * kHeads * kDv;
+    p.part_lse = p.part_out + ((size_t)num_wg + batch) * kHeads * kDv;
+    p.batch = batch;
     p.max_seqlen = max_seqlen_kv;
-    p.chunk_len = chunk_len;
-    p.splits_max = splits_max;
+    p.num_wg = num_wg;
     p.scale_log2e = scale * 1.4426950408889634f;
 
     hipStream_t hs = static_cast<hipStream_t>(stream);
-    if (phases & MLA_PHASE_SPLIT) {
-        hipLaunchKernelGGL(mla_decode_split_kernel, dim3(batch * splits_max), dim3(kThreads), kLdsBytes, hs, p);
+    if (flags & MLA_PHASE_SPLIT) {
+        hipLaunchKernelGGL(mla_decode_split_kernel, dim3(num_wg), dim3(kThreads), kLdsBytes, hs, p);
         if (hipGetLastError() != hipSuccess) return MLA_ERR_HIP;
     }
-    if (phases & MLA_PHASE_COMBINE) {
+    if (flags & MLA_PHASE_COMBINE) {
         hipLaunchKernelGGL(mla_decode_combine_kernel, dim3(batch * kHeads), dim3(kCombineThreads), 0, hs, p);
         if (hipGetLastError() != hipSuccess) return MLA_ERR_HIP;
     }
@@ -433,59 +603,51 @@ mla_status_t launch(const void *q, const void *kv_cache, int64_t kv_batch_stride
 
 extern "C" {
 
-mla_status_t mla_decode_workspace_size_for_chunk(int batch, int max_seqlen_kv, int chunk_len,
-                                                 size_t *bytes, int *num_splits_max) {
-    if (!bytes) return MLA_ERR_INVALID_ARG;
-    mla_status_t st = check_shape(batch, kHeads, max_seqlen_kv);
-    if (st != MLA_OK) return st;
-    if (chunk_len <= 0 || chunk_len % kChunkGranule != 0) return MLA_ERR_INVALID_ARG;
-    const int splits_max = (max_seqlen_kv + chunk_len - 1) / chunk_len;
-    *bytes = workspace_bytes_for(batch, splits_max);
-    if (num_splits_max) *num_splits_max = splits_max;
+// Automatic plan: persistent workgroups for 11/16 of the compute units.  One workgroup fills a
+// compute unit (LDS), and HBM is saturated well before every unit streams: on 256 units the
+// kernel is fastest with 160-192 workgroups; beyond that the extra requests only add contention
+// and pairs of XCDs stop sharing their path to memory evenly, so the slowest workgroup gets later.
+static mla_status_t planned_workgroups(int *num_wg) {
+    int dev = 0, cus = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return MLA_ERR_HIP;
+    if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0)
+        return MLA_ERR_HIP;
+    const int n = cus * 11 / 16;
+    *num_wg = n < 1 ? 1 : n;
     return MLA_OK;
 }
 
-mla_status_t mla_decode_workspace_size(int batch, int num_heads, int max_seqlen_kv, int num_cus,
-                                       size_t *bytes, int *chunk_len, int *num_splits_max) {
+mla_status_t mla_decode_workspace_size(int batch, int num_heads, int max_seqlen_kv, int num_workgroups,
+                                       size_t *bytes, int *num_workgroups_used) {
     if (!bytes) return MLA_ERR_INVALID_ARG;
     mla_status_t st = check_shape(batch, num_heads, max_seqlen_kv);
     if (st != MLA_OK) return st;
-    if (num_cus < 0) return MLA_ERR_INVALID_ARG;
-    if (num_cus == 0) {
-        int dev = 0;
-        if (hipGetDevice(&dev) != hipSuccess) return MLA_ERR_HIP;
-        if (hipDeviceGetAttribute(&num_cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || num_cus <= 0)
-            return MLA_ERR_HIP;
+    if (num_workgroups < 0 || num_workgroups > kMaxWorkgroups) return MLA_ERR_INVALID_ARG;
+    if (num_workgroups == 0) {
+        st = planned_workgroups(&num_workgroups);
+        if (st != MLA_OK) return st;
     }
-    const int chunk = plan_chunk_len(batch, max_seqlen_kv, num_cus);
-    if (chunk_len) *chunk_len = chunk;
-    return mla_decode_workspace_size_for_chunk(batch, max_seqlen_kv, chunk, bytes, num_splits_max);
-}
-
-static mla_status_t planned_chunk(int batch, int max_seqlen_kv, int *chunk) {
-    int dev = 0, num_cus = 0;
-    if (hipGetDevice(&dev) != hipSuccess) return MLA_ERR_HIP;
-    if (hipDeviceGetAttribute(&num_cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || num_cus <= 0)
-        return MLA_ERR_HIP;
-    *chunk = plan_chunk_len(batch, max_seqlen_kv, num_cus);
+    *bytes = workspace_bytes_for(batch, num_workgroups);
+    if (num_workgroups_used) *num_workgroups_used = num_workgroups;
     return MLA_OK;
 }
 
 mla_status_t mla_decode_ex(const void *q, const void *kv_cache, int64_t kv_batch_stride,
                            const int32_t *cache_seqlens, int batch, int num_heads, int max_seqlen_kv,
                            float scale, float *out, float *lse, void *workspace, size_t workspace_bytes,
-                           int chunk_len, int phases, void *stream) {
+                           int num_workgroups, int flags, void *stream) {
     mla_status_t st = validate(q, kv_cache, kv_batch_stride, cache_seqlens, batch, num_heads, max_seqlen_kv,
                                scale, out, lse, workspace);
     if (st != MLA_OK) return st;
-    if (chunk_len < 0 || chunk_len % kChunkGranule != 0) return MLA_ERR_INVALID_ARG;
-    if (phases <= 0 || (phases & ~(MLA_PHASE_SPLIT | MLA_PHASE_COMBINE)) != 0) return MLA_ERR_INVALID_ARG;
-    if (chunk_len == 0) {
-        st = planned_chunk(batch, max_seqlen_kv, &chunk_len);
+    if (num_workgroups < 0 || num_workgroups > kMaxWorkgroups) return MLA_ERR_INVALID_ARG;
+    if ((flags & ~(MLA_PHASE_SPLIT | MLA_PHASE_COMBINE)) != 0) return MLA_ERR_INVALID_ARG;
+    if ((flags & (MLA_PHASE_SPLIT | MLA_PHASE_COMBINE)) == 0) return MLA_ERR_INVALID_ARG;
+    if (num_workgroups == 0) {
+        st = planned_workgroups(&num_workgroups);
         if (st != MLA_OK) return st;
     }
     return launch(q, kv_cache, kv_batch_stride, cache_seqlens, batch, max_seqlen_kv, scale, out, lse,
-                  workspace, workspace_bytes, chunk_len, phases, stream);
+                  workspace, workspace_bytes, num_workgroups, flags, stream);
 }
 
 mla_status_t mla_decode(const void *q, const void *kv_cache, int64_t kv_batch_stride,

@@ -42,10 +42,8 @@ def lib():
         L = ctypes.CDLL(LIB_PATH)
         vp, ci, sz = ctypes.c_void_p, ctypes.c_int, ctypes.c_size_t
         szp, cip = ctypes.POINTER(ctypes.c_size_t), ctypes.POINTER(ctypes.c_int)
-        L.mla_decode_workspace_size.argtypes = [ci, ci, ci, ci, szp, cip, cip]
+        L.mla_decode_workspace_size.argtypes = [ci, ci, ci, ci, szp, cip]
         L.mla_decode_workspace_size.restype = ci
-        L.mla_decode_workspace_size_for_chunk.argtypes = [ci, ci, ci, szp, cip]
-        L.mla_decode_workspace_size_for_chunk.restype = ci
         L.mla_decode.argtypes = [vp, vp, ctypes.c_int64, vp, ci, ci, ci, ctypes.c_float, vp, vp, vp, sz, vp]
         L.mla_decode.restype = ci
         L.mla_decode_ex.argtypes = [vp, vp, ctypes.c_int64, vp, ci, ci, ci, ctypes.c_float, vp, vp,
@@ -57,24 +55,14 @@ def lib():
     return _lib
 
 
-def mla_decode_workspace_size(batch, num_heads, max_seqlen_kv, num_cus=0):
-    """-> (bytes, chunk_len, num_splits_max).  num_cus=0 asks the current device."""
-    nbytes, chunk, splits = ctypes.c_size_t(0), ctypes.c_int(0), ctypes.c_int(0)
-    st = lib().mla_decode_workspace_size(batch, num_heads, max_seqlen_kv, num_cus,
-                                         ctypes.byref(nbytes), ctypes.byref(chunk), ctypes.byref(splits))
+def mla_decode_workspace_size(batch, num_heads, max_seqlen_kv, num_workgroups=0):
+    """-> (bytes, num_workgroups_used).  num_workgroups=0 is the automatic plan (asks the device)."""
+    nbytes, used = ctypes.c_size_t(0), ctypes.c_int(0)
+    st = lib().mla_decode_workspace_size(batch, num_heads, max_seqlen_kv, num_workgroups,
+                                         ctypes.byref(nbytes), ctypes.byref(used))
     if st != MLA_OK:
         raise MlaError(st, "mla_decode_workspace_size")
-    return nbytes.value, chunk.value, splits.value
-
-
-def mla_decode_workspace_size_for_chunk(batch, max_seqlen_kv, chunk_len):
-    """-> (bytes, num_splits_max) for a forced chunk length."""
-    nbytes, splits = ctypes.c_size_t(0), ctypes.c_int(0)
-    st = lib().mla_decode_workspace_size_for_chunk(batch, max_seqlen_kv, chunk_len,
-                                                   ctypes.byref(nbytes), ctypes.byref(splits))
-    if st != MLA_OK:
-        raise MlaError(st, "mla_decode_workspace_size_for_chunk")
-    return nbytes.value, splits.value
+    return nbytes.value, used.value
 
 
 def _check_tensors(q, kv_cache, cache_seqlens):
@@ -98,23 +86,20 @@ PHASE_SPLIT = 1
 PHASE_COMBINE = 2
 
 
-def mla_decode(q, kv_cache, cache_seqlens, scale, out=None, lse=None, workspace=None, chunk_len=None,
+def mla_decode(q, kv_cache, cache_seqlens, scale, out=None, lse=None, workspace=None, num_workgroups=None,
                phases=None):
     """out [batch, 1, heads, 512] fp32, lse [batch, heads] fp32 on the current stream (asynchronous).
 
     q [batch, 1, 16, 576] bf16, kv_cache [batch, max_seqlen_kv, 576] bf16 (batch stride free),
     cache_seqlens [batch] int32, all on the current device.  ``out``, ``lse`` and ``workspace``
-    (a uint8 tensor) are allocated with torch when not given.  ``chunk_len`` forces the split plan
-    and ``phases`` selects the kernels (both go through ``mla_decode_ex``).
+    (a uint8 tensor) are allocated with torch when not given.  ``num_workgroups`` forces the
+    split plan and ``phases`` selects the kernels (both go through ``mla_decode_ex``).
     """
     _check_tensors(q, kv_cache, cache_seqlens)
     batch, _, heads, _ = q.shape
     max_seqlen = kv_cache.shape[1]
     dev = q.device
-    if chunk_len is None:
-        need, _, _ = mla_decode_workspace_size(batch, heads, max_seqlen, 0)
-    else:
-        need, _ = mla_decode_workspace_size_for_chunk(batch, max_seqlen, chunk_len)
+    need, _ = mla_decode_workspace_size(batch, heads, max_seqlen, int(num_workgroups or 0))
     if out is None:
         out = torch.empty((batch, 1, heads, D_V), dtype=torch.float32, device=dev)
     if lse is None:
@@ -126,11 +111,11 @@ def mla_decode(q, kv_cache, cache_seqlens, scale, out=None, lse=None, workspace=
             ctypes.c_void_p(cache_seqlens.data_ptr()), batch, heads, max_seqlen, float(scale),
             ctypes.c_void_p(out.data_ptr()), ctypes.c_void_p(lse.data_ptr()),
             ctypes.c_void_p(workspace.data_ptr()), workspace.numel() * workspace.element_size()]
-    if chunk_len is None and phases is None:
+    if num_workgroups is None and phases is None:
         st = lib().mla_decode(*args, stream)
         where = "mla_decode"
     else:
-        st = lib().mla_decode_ex(*args, int(chunk_len or 0),
+        st = lib().mla_decode_ex(*args, int(num_workgroups or 0),
                                  int(PHASE_SPLIT | PHASE_COMBINE if phases is None else phases), stream)
         where = "mla_decode_ex"
     if st != MLA_OK:

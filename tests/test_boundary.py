@@ -20,8 +20,7 @@ def _declared_functions():
 
 def test_library_exports_every_declared_symbol():
     names = _declared_functions()
-    assert {"mla_decode", "mla_decode_ex", "mla_decode_workspace_size",
-            "mla_decode_workspace_size_for_chunk", "mla_status_string"} <= set(names)
+    assert {"mla_decode", "mla_decode_ex", "mla_decode_workspace_size", "mla_status_string"} <= set(names)
     lib = mla.lib()
     for n in names:
         assert hasattr(lib, n), n
@@ -34,46 +33,32 @@ def test_status_strings():
     assert lib.mla_status_string(99)
 
 
-@pytest.mark.parametrize("batch,seqlen", [(1, 512), (16, 4096), (16, 16384), (16, 65536), (32, 65536), (1, 1), (3, 100000)])
-def test_plan_covers_the_sequence_and_fills_the_cus(batch, seqlen):
-    nbytes, chunk, splits = mla.mla_decode_workspace_size(batch, 16, seqlen, num_cus=256)
-    assert chunk % 128 == 0 and chunk >= 128
-    assert (splits - 1) * chunk < seqlen <= splits * chunk
-    per_split = 16 * 512 * 4 + 16 * 4
-    assert nbytes >= batch * splits * per_split
-    assert nbytes <= batch * splits * per_split + 16
-    # enough workgroups for 256 compute units whenever the problem is large enough
-    if batch * seqlen >= 256 * 512:
-        assert batch * splits >= 256
-    nb2, sp2 = mla.mla_decode_workspace_size_for_chunk(batch, seqlen, chunk)
-    assert (nb2, sp2) == (nbytes, splits)
-
-
-def test_plan_is_deterministic_and_scales_with_cus():
-    a = mla.mla_decode_workspace_size(16, 16, 65536, num_cus=256)
-    b = mla.mla_decode_workspace_size(16, 16, 65536, num_cus=256)
-    c = mla.mla_decode_workspace_size(16, 16, 65536, num_cus=64)
-    assert a == b
-    assert c[1] >= a[1]          # fewer compute units -> longer chunks
+@pytest.mark.parametrize("batch,num_wg", [(1, 256), (16, 256), (32, 304), (3, 1), (1024, 64)])
+def test_workspace_size_is_one_slot_per_workgroup_and_sequence(batch, num_wg):
+    nbytes, used = mla.mla_decode_workspace_size(batch, 16, 65536, num_workgroups=num_wg)
+    assert used == num_wg
+    slot = 16 * 512 * 4 + 16 * 4
+    assert (num_wg + batch) * slot <= nbytes <= (num_wg + batch) * slot + 16
+    # independent of the KV length: the lengths live on the device
+    assert mla.mla_decode_workspace_size(batch, 16, 7, num_workgroups=num_wg) == (nbytes, used)
 
 
 def test_workspace_size_errors():
     lib = mla.lib()
     n = ctypes.c_size_t(0)
-    assert lib.mla_decode_workspace_size(16, 8, 4096, 256, ctypes.byref(n), None, None) == mla.MLA_ERR_UNSUPPORTED_SHAPE
-    assert lib.mla_decode_workspace_size(0, 16, 4096, 256, ctypes.byref(n), None, None) == mla.MLA_ERR_INVALID_ARG
-    assert lib.mla_decode_workspace_size(16, 16, 0, 256, ctypes.byref(n), None, None) == mla.MLA_ERR_INVALID_ARG
-    assert lib.mla_decode_workspace_size(16, 16, 4096, -1, ctypes.byref(n), None, None) == mla.MLA_ERR_INVALID_ARG
-    assert lib.mla_decode_workspace_size(16, 16, 4096, 256, None, None, None) == mla.MLA_ERR_INVALID_ARG
-    assert lib.mla_decode_workspace_size_for_chunk(16, 4096, 100, ctypes.byref(n), None) == mla.MLA_ERR_INVALID_ARG
-    assert lib.mla_decode_workspace_size_for_chunk(16, 4096, 0, ctypes.byref(n), None) == mla.MLA_ERR_INVALID_ARG
+    assert lib.mla_decode_workspace_size(16, 8, 4096, 256, ctypes.byref(n), None) == mla.MLA_ERR_UNSUPPORTED_SHAPE
+    assert lib.mla_decode_workspace_size(0, 16, 4096, 256, ctypes.byref(n), None) == mla.MLA_ERR_INVALID_ARG
+    assert lib.mla_decode_workspace_size(16, 16, 0, 256, ctypes.byref(n), None) == mla.MLA_ERR_INVALID_ARG
+    assert lib.mla_decode_workspace_size(16, 16, 4096, -1, ctypes.byref(n), None) == mla.MLA_ERR_INVALID_ARG
+    assert lib.mla_decode_workspace_size(16, 16, 4096, 1 << 20, ctypes.byref(n), None) == mla.MLA_ERR_INVALID_ARG
+    assert lib.mla_decode_workspace_size(16, 16, 4096, 256, None, None) == mla.MLA_ERR_INVALID_ARG
 
 
 def _call(q=0x1000, kv=0x2000, stride=4096 * 576, lens=0x3000, batch=2, heads=16, seqlen=4096, scale=0.1,
-          out=0x4000, lse=0x5000, ws=0x6000, ws_bytes=1 << 30, chunk=256, phases=3):
+          out=0x4000, lse=0x5000, ws=0x6000, ws_bytes=1 << 30, num_wg=256, phases=3):
     vp = ctypes.c_void_p
     return mla.lib().mla_decode_ex(vp(q), vp(kv), stride, vp(lens), batch, heads, seqlen, scale, vp(out), vp(lse),
-                                   vp(ws), ws_bytes, chunk, phases, None)
+                                   vp(ws), ws_bytes, num_wg, phases, None)
 
 
 def test_decode_argument_errors_come_before_any_device_work():
@@ -96,11 +81,12 @@ def test_decode_argument_errors_come_before_any_device_work():
     assert _call(stride=4096 * 576 + 4) == E.MLA_ERR_INVALID_ARG  # breaks 16-byte alignment of rows
     assert _call(scale=float("nan")) == E.MLA_ERR_INVALID_ARG
     assert _call(scale=float("inf")) == E.MLA_ERR_INVALID_ARG
-    assert _call(chunk=100) == E.MLA_ERR_INVALID_ARG
-    assert _call(chunk=-128) == E.MLA_ERR_INVALID_ARG
+    assert _call(num_wg=-1) == E.MLA_ERR_INVALID_ARG
+    assert _call(num_wg=1 << 20) == E.MLA_ERR_INVALID_ARG
     assert _call(phases=0) == E.MLA_ERR_INVALID_ARG
-    assert _call(phases=4) == E.MLA_ERR_INVALID_ARG
-    need, _ = mla.mla_decode_workspace_size_for_chunk(2, 4096, 256)
+    assert _call(phases=4) == E.MLA_ERR_INVALID_ARG     # no phase selected
+    assert _call(phases=8) == E.MLA_ERR_INVALID_ARG
+    need, _ = mla.mla_decode_workspace_size(2, 16, 4096, 256)
     assert _call(ws_bytes=need - 1) == E.MLA_ERR_WORKSPACE_TOO_SMALL
 
 

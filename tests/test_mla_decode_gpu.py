@@ -26,12 +26,12 @@ def _dev():
     return torch.device("cuda:0")
 
 
-def _run(q, kv, lens, scale=inputs.SCALE, chunk_len=None, kv_dev=None):
+def _run(q, kv, lens, scale=inputs.SCALE, num_wg=None, kv_dev=None):
     dev = _dev()
     qd = q.to(dev)
     kvd = kv.to(dev) if kv_dev is None else kv_dev
     ld = lens.to(dev)
-    out, lse = mla.mla_decode(qd, kvd, ld, scale, chunk_len=chunk_len)
+    out, lse = mla.mla_decode(qd, kvd, ld, scale, num_workgroups=num_wg)
     torch.cuda.synchronize()
     return out.cpu().numpy().reshape(q.shape[0], q.shape[2], inputs.D_V).astype(np.float64), lse.cpu().numpy().astype(np.float64)
 
@@ -55,24 +55,24 @@ def _oracle(oracle, q, kv, lens, scale=inputs.SCALE):
 
 # ---- small cases: several tiles, ragged tails, every split count ---------------------------------
 
-@pytest.mark.parametrize("chunk_len", [None, 128, 256, 1024])
-def test_small_ragged_elementwise(oracle, chunk_len):
+@pytest.mark.parametrize("num_wg", [None, 1, 2, 7, 40, 1000])
+def test_small_ragged_elementwise(oracle, num_wg):
     lens = [1, 31, 32, 33, 127, 128, 129, 700, 1000, 95, 513, 640]
     q, kv, l = inputs.make_inputs(len(lens), 1000, lens, seed=101, poison_tail=True)
     ref_o, ref_l = _oracle(oracle, q, kv, l)
-    print("case small_ragged chunk", chunk_len, flush=True)
-    out, lse = _run(q, kv, l, chunk_len=chunk_len)
-    _check(out, lse, ref_o, ref_l, label="small_ragged chunk=%s" % chunk_len)
+    print("case small_ragged num_wg", num_wg, flush=True)
+    out, lse = _run(q, kv, l, num_wg=num_wg)
+    _check(out, lse, ref_o, ref_l, label="small_ragged num_wg=%s" % num_wg)
 
 
 def test_empty_and_full_sequences(oracle):
     lens = [0, 384, 0, 1]
     q, kv, l = inputs.make_inputs(4, 384, lens, seed=102, poison_tail=True)
     ref_o, ref_l = _oracle(oracle, q, kv, l)
-    for chunk in (None, 128):
-        print("case empty_and_full chunk", chunk, flush=True)
-        out, lse = _run(q, kv, l, chunk_len=chunk)
-        _check(out, lse, ref_o, ref_l, label="empty/full chunk=%s" % chunk)
+    for nwg in (None, 1, 3, 5):
+        print("case empty_and_full num_wg", nwg, flush=True)
+        out, lse = _run(q, kv, l, num_wg=nwg)
+        _check(out, lse, ref_o, ref_l, label="empty/full num_wg=%s" % nwg)
         assert (out[0] == 0).all() and (out[2] == 0).all()
         assert np.isneginf(lse[0]).all() and np.isneginf(lse[2]).all()
 
@@ -108,9 +108,9 @@ def test_growing_scores_exercise_the_rescale_path(oracle):
     kv = (kv.float() * ramp).to(torch.bfloat16)
     ref_o, ref_l = _oracle(oracle, q, kv, l)
     assert ref_l.min() > 20                  # maxima climb by far more than the lazy threshold
-    for chunk in (None, 2048):
-        print("case growing_scores chunk", chunk, flush=True)
-        out, lse = _run(q, kv, l, chunk_len=chunk)
+    for nwg in (None, 1, 2):
+        print("case growing_scores num_wg", nwg, flush=True)
+        out, lse = _run(q, kv, l, num_wg=nwg)
         # |v| grows to ~20, so the absolute bounds scale with it
         err = np.abs(out - ref_o)
         rel = err.max() / np.abs(ref_o).max()
@@ -122,19 +122,19 @@ def test_growing_scores_exercise_the_rescale_path(oracle):
 def test_split_choice_does_not_change_the_result_beyond_rounding():
     q, kv, l = inputs.make_inputs(4, 4096, [4096, 3000, 129, 2048], seed=106)
     print("case split_choice", flush=True)
-    base_o, base_l = _run(q, kv, l, chunk_len=4096)
-    for chunk in (128, 512, 1536):
-        o, s = _run(q, kv, l, chunk_len=chunk)
+    base_o, base_l = _run(q, kv, l, num_wg=1)
+    for nwg in (2, 3, 16, 75, 256):
+        o, s = _run(q, kv, l, num_wg=nwg)
         assert np.abs(o - base_o).max() < 1e-5
         assert np.abs(s - base_l).max() < 1e-5
 
 
-def test_repeat_is_bit_identical_and_workspace_contents_do_not_matter():
+def test_repeat_is_bit_identical_and_workspace_contents_do_not_matter(oracle):
     dev = _dev()
     q, kv, l = inputs.make_inputs(5, 3000, [3000, 2999, 1, 1500, 640], seed=107, poison_tail=True)
     qd, kvd, ld = q.to(dev), kv.to(dev), l.to(dev)
-    need, chunk, splits = mla.mla_decode_workspace_size(5, 16, 3000, 0)
-    print("case repeat chunk", chunk, "splits", splits, flush=True)
+    need, nwg = mla.mla_decode_workspace_size(5, 16, 3000, 0)
+    print("case repeat num_wg", nwg, flush=True)
     ws = torch.empty((need,), dtype=torch.uint8, device=dev)
     outs = []
     for fill in (0x00, 0xFF, 0x7F):          # 0xFF.. and 0x7F7F.. are NaN / huge as fp32
@@ -146,21 +146,23 @@ def test_repeat_is_bit_identical_and_workspace_contents_do_not_matter():
         outs.append((out.cpu(), lse.cpu()))
     for o, s in outs[1:]:
         assert torch.equal(o, outs[0][0]) and torch.equal(s, outs[0][1])
-    assert torch.isfinite(outs[0][0]).all() and torch.isfinite(outs[0][1]).all()
+    ref_o, ref_l = _oracle(oracle, q, kv, l)
+    _check(outs[0][0].numpy().reshape(5, 16, 512).astype(np.float64), outs[0][1].numpy().astype(np.float64),
+           ref_o, ref_l, label="repeat")
 
 
 def test_phases_split_then_combine_equals_one_call():
     dev = _dev()
     q, kv, l = inputs.make_inputs(2, 1024, [1024, 600], seed=108)
     qd, kvd, ld = q.to(dev), kv.to(dev), l.to(dev)
-    need, _ = mla.mla_decode_workspace_size_for_chunk(2, 1024, 256)
+    need, _ = mla.mla_decode_workspace_size(2, 16, 1024, 5)
     ws = torch.zeros((need,), dtype=torch.uint8, device=dev)
     print("case phases", flush=True)
-    o1, s1 = mla.mla_decode(qd, kvd, ld, inputs.SCALE, workspace=ws, chunk_len=256)
+    o1, s1 = mla.mla_decode(qd, kvd, ld, inputs.SCALE, workspace=ws, num_workgroups=5)
     torch.cuda.synchronize()
     o2 = torch.zeros_like(o1); s2 = torch.zeros_like(s1)
-    mla.mla_decode(qd, kvd, ld, inputs.SCALE, out=o2, lse=s2, workspace=ws, chunk_len=256, phases=mla.PHASE_SPLIT)
-    mla.mla_decode(qd, kvd, ld, inputs.SCALE, out=o2, lse=s2, workspace=ws, chunk_len=256, phases=mla.PHASE_COMBINE)
+    mla.mla_decode(qd, kvd, ld, inputs.SCALE, out=o2, lse=s2, workspace=ws, num_workgroups=5, phases=mla.PHASE_SPLIT)
+    mla.mla_decode(qd, kvd, ld, inputs.SCALE, out=o2, lse=s2, workspace=ws, num_workgroups=5, phases=mla.PHASE_COMBINE)
     torch.cuda.synchronize()
     assert torch.equal(o1, o2) and torch.equal(s1, s2)
 
