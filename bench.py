@@ -25,6 +25,45 @@ TRAFFIC_FILE = os.path.join(ROOT, "profiles", "mla_decode_split_b16_kv64k_traffi
 CPU_SAMPLE_SEQS = 16            # sequences of the batch the oracle is timed on (about 15 s of CPU work)
 
 
+def sweep(torch, inputs, mla, dev, args):
+    """Whole-call time over the grid of the paper's Figure 1 (Section 4.1: batch 16 and 32, KV length
+    512 ... 64K, one query token, 16 heads).  Values are drawn on the device (timing only; parity over
+    these shapes is the job of the tests).  KV buffers are rotated so that consecutive calls cannot be
+    served from the 256 MB last-level cache."""
+    g = torch.Generator(device=dev).manual_seed(inputs.BASE_SEED)
+    for batch in (16, 32):
+        for n in (512, 1024, 2048, 4096, 8192, 16384, 32768, 65536):
+            kv_bytes = batch * n * inputs.D_QK * 2
+            n_buf = max(2, min(64, -(-(512 << 20) // kv_bytes)))
+            dt = torch.float16 if args.dtype == "fp16" else torch.bfloat16
+            q = torch.randn((batch, 1, 16, inputs.D_QK), device=dev, generator=g).to(dt)
+            kvs = [torch.randn((batch, n, inputs.D_QK), device=dev, generator=g).to(dt)
+                   for _ in range(n_buf)]
+            lens = torch.full((batch,), n, dtype=torch.int32, device=dev)
+            need, nwg = mla.mla_decode_workspace_size(batch, 16, n, args.workgroups)
+            ws = torch.empty((need,), dtype=torch.uint8, device=dev)
+            out = torch.empty((batch, 1, 16, 512), dtype=torch.float32, device=dev)
+            lse = torch.empty((batch, 16), dtype=torch.float32, device=dev)
+
+            def step(i):
+                mla.mla_decode(q, kvs[i % n_buf], lens, inputs.SCALE, out=out, lse=lse, workspace=ws,
+                               num_workgroups=args.workgroups or None)
+            for i in range(args.warmup):
+                step(i)
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for i in range(args.steps):
+                step(i)
+            torch.cuda.synchronize()
+            us = (time.perf_counter() - t0) / args.steps * 1e6
+            alg = inputs.algorithmic_bytes([n] * batch)
+            print(json.dumps({"dtype": args.dtype, "batch": batch, "kv_len": n, "us_per_call": round(us, 2),
+                              "tb_per_s": round(alg / us / 1e6, 3),
+                              "tflops_paper_style": round(inputs.algorithmic_flops([n] * batch) / us / 1e6, 1),
+                              "workgroups": nwg, "kv_buffers_rotated": n_buf}), flush=True)
+            del kvs
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -33,6 +72,11 @@ def main():
     ap.add_argument("--config", type=int, default=4, help="benchmark configuration id (4 = headline)")
     ap.add_argument("--workgroups", type=int, default=0, help="force the number of workgroups (0 = automatic)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--dtype", choices=("bf16", "fp16"), default="bf16",
+                    help="element type of q and the KV cache (bf16 = the headline metric; fp16 = the paper's own)")
+    ap.add_argument("--sweep", action="store_true",
+                    help="time the whole call over batch 16 and 32 x KV length 512 ... 64K (the grid of the "
+                         "paper's Figure 1) and print one JSON line per point instead of the benchmark line")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="only run a plain device-to-device copy of 1 GiB five times (counter calibration "
                          "for rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE) and exit")
@@ -62,8 +106,13 @@ def main():
                           "copies": 5}))
         return
 
+    if args.sweep:
+        sweep(torch, inputs, mla, dev, args)
+        return
+
     cfg = inputs.CONFIGS[args.config]
-    q, kv, lens = inputs.make_config(args.config)
+    dt = torch.float16 if args.dtype == "fp16" else torch.bfloat16
+    q, kv, lens = inputs.make_config(args.config, dtype=dt)
     batch, max_seqlen = cfg["batch"], cfg["seqlen"]
     alg_bytes = inputs.algorithmic_bytes(lens.tolist())
     alg_flops = inputs.algorithmic_flops(lens.tolist())
@@ -121,7 +170,7 @@ def main():
     achieved_gbps = alg_bytes / (split_ms_avg * 1e-3) / 1e9
 
     traffic = None
-    if args.config == 4 and os.path.exists(TRAFFIC_FILE):
+    if args.config == 4 and args.dtype == "bf16" and os.path.exists(TRAFFIC_FILE):
         try:
             traffic = json.load(open(TRAFFIC_FILE)).get("hbm_bytes_per_launch")
         except (OSError, ValueError):
@@ -133,9 +182,11 @@ def main():
         from oracle import mla_oracle
         ns = min(CPU_SAMPLE_SEQS, batch)
         qs, kvsamp, ls = q[:ns], kv[:ns], lens[:ns]
-        qb, kvb = inputs.bf16_bits(qs), inputs.bf16_bits(kvsamp)
+        qb, kvb = inputs.bits16(qs), inputs.bits16(kvsamp)
         t0 = time.perf_counter()
-        ref_o, ref_l = mla_oracle.decode(qb, kvb, ls.numpy(), inputs.SCALE, inputs.D_V)
+        ref_o, ref_l = mla_oracle.decode_general(qb, kvb, ls.numpy(), inputs.SCALE, inputs.D_V,
+                                                 dtype=mla_oracle.F16 if args.dtype == "fp16" else mla_oracle.BF16)
+        ref_o = ref_o[:, 0]
         cpu_s = time.perf_counter() - t0
         sample_bytes = inputs.algorithmic_bytes(ls.tolist())
         # the same sample doubles as a sanity check of the benchmarked output
@@ -150,10 +201,10 @@ def main():
     line = {
         "metric": METRIC, "value": tbps, "unit": "TB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_per_step, "us_per_call": ms_per_step * 1e3, "higher_is_better": True, "scaling": "weak",
-        "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": "config %d: MLA decode batch %d, q_len 1, 16 heads, shared 576-d bf16 latent KV, "
+        "vs_baseline": None, "dtype": args.dtype, "data": "synthetic",
+        "config": {"workload": "config %d: MLA decode batch %d, q_len 1, 16 heads, shared 576-d %s latent KV, "
                                "KV length %s, scale 1/sqrt(192), d_v 512" % (
-                                   args.config, batch, "%d per sequence" % max_seqlen if cfg["ragged"] is None
+                                   args.config, batch, args.dtype, "%d per sequence" % max_seqlen if cfg["ragged"] is None
                                    else "ragged uniform[%d,%d]" % cfg["ragged"]),
                    "total_kv_tokens": int(lens.sum()), "algorithmic_bytes_per_call": alg_bytes,
                    "algorithmic_flops_per_call": alg_flops, "workgroups": nwg_used,

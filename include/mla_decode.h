@@ -117,6 +117,22 @@ mla_status_t mla_decode_ex(const void *q, const void *kv_cache, int64_t kv_batch
                            void *workspace, size_t workspace_bytes, int num_workgroups,
                            int flags, void *stream);
 
+/*
+ * The same call for either 16-bit input type.  The paper's own runs are FP16 (Section 4.1);
+ * the matrix-core products then take fp16 operands, and the softmax probabilities enter the
+ * second product as ONE fp16 term (11 significant bits) instead of the two-term bf16 split.
+ *   dtype  MLA_DTYPE_BF16 or MLA_DTYPE_F16: the element type of q and kv_cache (out and lse
+ *          stay fp32); any other value is MLA_ERR_INVALID_ARG.
+ * All other arguments, layouts and error behaviour are those of mla_decode_ex().
+ */
+#define MLA_DTYPE_BF16 0
+#define MLA_DTYPE_F16 1
+mla_status_t mla_decode_typed(const void *q, const void *kv_cache, int64_t kv_batch_stride,
+                              const int32_t *cache_seqlens, int batch, int num_heads,
+                              int max_seqlen_kv, int dtype, float scale, float *out, float *lse,
+                              void *workspace, size_t workspace_bytes, int num_workgroups,
+                              int flags, void *stream);
+
 /* Static string for a status code (never NULL). */
 const char *mla_status_string(mla_status_t status);
 

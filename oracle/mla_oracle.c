@@ -46,13 +46,41 @@ static double bf16_to_double(uint16_t bits)
     return (double)f;
 }
 
-/* scaled score of head h of sequence b against token t */
-static double score(const uint16_t *q_bh, const uint16_t *k_t, int d_qk, double scale)
+/*
+ * IEEE binary16 (1 sign, 5 exponent, 10 fraction bits) decoded exactly: the paper's own runs
+ * use FP16 inputs (Section 4.1).  Subnormals are fraction * 2^-24, exponent 31 is inf / NaN.
+ */
+static double f16_to_double(uint16_t bits)
+{
+    int sign = bits >> 15, e = (bits >> 10) & 31, f = bits & 1023;
+    double v;
+    if (e == 0) v = ldexp((double)f, -24);
+    else if (e == 31) v = f ? NAN : INFINITY;
+    else v = ldexp((double)(1024 + f), e - 25);
+    return sign ? -v : v;
+}
+
+/* input element types */
+#define ORACLE_BF16 0
+#define ORACLE_F16 1
+
+static double elem(uint16_t bits, int dtype)
+{
+    return dtype == ORACLE_F16 ? f16_to_double(bits) : bf16_to_double(bits);
+}
+
+/* scaled score of one query row against token t */
+static double score_t(const uint16_t *q_bh, const uint16_t *k_t, int d_qk, double scale, int dtype)
 {
     double acc = 0.0;
     for (int c = 0; c < d_qk; ++c)
-        acc += bf16_to_double(q_bh[c]) * bf16_to_double(k_t[c]);
+        acc += elem(q_bh[c], dtype) * elem(k_t[c], dtype);
     return scale * acc;
+}
+
+static double score(const uint16_t *q_bh, const uint16_t *k_t, int d_qk, double scale)
+{
+    return score_t(q_bh, k_t, d_qk, scale, ORACLE_BF16);
 }
 
 /*
@@ -60,9 +88,9 @@ static double score(const uint16_t *q_bh, const uint16_t *k_t, int d_qk, double 
  * Writes out[d_v] and *lse.  Section 3.1 definition + Algorithm 1's L.
  * scratch: t1 - t0 doubles.
  */
-static void attend_range(const uint16_t *q_bh, const uint16_t *kv_b, int d_qk, int d_v,
-                         int t0, int t1, double scale, double *out, double *lse,
-                         double *scratch)
+static void attend_range_t(const uint16_t *q_bh, const uint16_t *kv_b, int d_qk, int d_v,
+                           int t0, int t1, double scale, double *out, double *lse,
+                           double *scratch, int dtype)
 {
     int n = t1 - t0;
     if (n <= 0) {
@@ -73,7 +101,7 @@ static void attend_range(const uint16_t *q_bh, const uint16_t *kv_b, int d_qk, i
     /* pass 1: scores and their maximum */
     double m = -INFINITY;
     for (int t = 0; t < n; ++t) {
-        scratch[t] = score(q_bh, kv_b + (size_t)(t0 + t) * d_qk, d_qk, scale);
+        scratch[t] = score_t(q_bh, kv_b + (size_t)(t0 + t) * d_qk, d_qk, scale, dtype);
         if (scratch[t] > m) m = scratch[t];
     }
     /* pass 2: exponentials and their sum */
@@ -86,10 +114,55 @@ static void attend_range(const uint16_t *q_bh, const uint16_t *kv_b, int d_qk, i
     for (int d = 0; d < d_v; ++d) {
         double acc = 0.0;
         for (int t = 0; t < n; ++t)
-            acc += scratch[t] * bf16_to_double(kv_b[(size_t)(t0 + t) * d_qk + d]);
+            acc += scratch[t] * elem(kv_b[(size_t)(t0 + t) * d_qk + d], dtype);
         out[d] = acc / l;
     }
     *lse = m + log(l);
+}
+
+static void attend_range(const uint16_t *q_bh, const uint16_t *kv_b, int d_qk, int d_v,
+                         int t0, int t1, double scale, double *out, double *lse,
+                         double *scratch)
+{
+    attend_range_t(q_bh, kv_b, d_qk, d_v, t0, t1, scale, out, lse, scratch, ORACLE_BF16);
+}
+
+/*
+ * General form: q_len query tokens per sequence and either 16-bit input type.
+ *   q    [batch][q_len][heads][d_qk],  out [batch][q_len][heads][d_v],  lse [batch][q_len][heads]
+ *   seqlens[b] = N_b counts the KV rows INCLUDING those of the q_len new tokens.
+ * The paper's Section 3.1 notes that decoding feeds one or two tokens per step.  With
+ * more than one, the new tokens are the last q_len rows of the cache and attention is causal among
+ * them: query token j (0-based) sees rows [0, N_b - (q_len - 1 - j)), i.e. the last query token
+ * sees everything and each earlier one sees one row less.  q_len = 1 is the plain case.
+ *   dtype  0 = bf16 bit patterns, 1 = IEEE fp16 bit patterns (q and kv alike)
+ */
+int mla_oracle_decode_general(const uint16_t *q, const uint16_t *kv, int64_t kv_batch_stride,
+                              const int32_t *seqlens, int batch, int q_len, int heads, int d_qk,
+                              int d_v, int dtype, double scale, double *out, double *lse,
+                              int nthreads)
+{
+    if (!q || !kv || !seqlens || !out || !lse || batch < 0 || q_len <= 0 || heads <= 0 ||
+        d_qk <= 0 || d_v <= 0 || d_v > d_qk || (dtype != ORACLE_BF16 && dtype != ORACLE_F16))
+        return -1;
+    int fail = 0;
+    int rows = batch * q_len * heads;
+#ifdef _OPENMP
+    if (nthreads > 0) omp_set_num_threads(nthreads);
+#endif
+    (void)nthreads;
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int r = 0; r < rows; ++r) {
+        int b = r / (q_len * heads), j = (r / heads) % q_len;
+        int n = seqlens[b] - (q_len - 1 - j);      /* causal among the new tokens */
+        if (n < 0) n = 0;
+        double *scratch = (double *)malloc(sizeof(double) * (size_t)(n > 0 ? n : 1));
+        if (!scratch) { fail = 1; continue; }
+        attend_range_t(q + (size_t)r * d_qk, kv + (size_t)b * kv_batch_stride, d_qk, d_v, 0, n,
+                       scale, out + (size_t)r * d_v, lse + r, scratch, dtype);
+        free(scratch);
+    }
+    return fail ? -1 : 0;
 }
 
 /*

@@ -45,6 +45,8 @@ def _load():
         ci, cd, i64 = ctypes.c_int, ctypes.c_double, ctypes.c_int64
         lib.mla_oracle_decode.argtypes = [u16p, u16p, i64, i32p, ci, ci, ci, ci, cd, f64p, f64p, ci]
         lib.mla_oracle_decode.restype = ci
+        lib.mla_oracle_decode_general.argtypes = [u16p, u16p, i64, i32p, ci, ci, ci, ci, ci, ci, cd, f64p, f64p, ci]
+        lib.mla_oracle_decode_general.restype = ci
         lib.mla_oracle_decode_range.argtypes = [u16p, u16p, i64, i32p, ci, ci, ci, ci, ci, ci, cd, f64p, f64p]
         lib.mla_oracle_decode_range.restype = ci
         lib.mla_oracle_decode_transposed.argtypes = [u16p, u16p, i64, i32p, ci, ci, ci, ci, cd, f64p, f64p]
@@ -102,6 +104,37 @@ def decode(q_bits, kv_bits, seqlens, scale, d_v, nthreads=0):
                                _ptr(out, ctypes.c_double), _ptr(lse, ctypes.c_double), int(nthreads))
     if rc != 0:
         raise RuntimeError("mla_oracle_decode failed")
+    return out, lse
+
+
+BF16, F16 = 0, 1
+
+
+def decode_general(q_bits, kv_bits, seqlens, scale, d_v, dtype=BF16, nthreads=0):
+    """q_len query tokens per sequence (causal among themselves) and bf16 or fp16 bit patterns.
+
+    q_bits [batch, q_len, heads, d_qk] uint16, kv_bits [batch, max_seqlen, d_qk] uint16;
+    seqlens count the KV rows including the q_len new tokens.
+    Returns (out [batch, q_len, heads, d_v] f64, lse [batch, q_len, heads] f64).
+    """
+    lib = _load()
+    q_bits, kv_bits = _u16(q_bits), _u16(kv_bits)
+    if q_bits.ndim != 4:
+        raise ValueError("q must be [batch, q_len, heads, d_qk]")
+    batch, q_len, heads, d_qk = q_bits.shape
+    if kv_bits.ndim != 3 or kv_bits.shape[0] != batch or kv_bits.shape[2] != d_qk:
+        raise ValueError("kv must be [batch, max_seqlen, d_qk]")
+    seqlens = np.ascontiguousarray(seqlens, dtype=np.int32)
+    if seqlens.shape != (batch,) or (seqlens < 0).any() or (seqlens > kv_bits.shape[1]).any():
+        raise ValueError("seqlens must be [batch] with 0 <= len <= max_seqlen")
+    out = np.empty((batch, q_len, heads, d_v), dtype=np.float64)
+    lse = np.empty((batch, q_len, heads), dtype=np.float64)
+    rc = lib.mla_oracle_decode_general(_ptr(q_bits, ctypes.c_uint16), _ptr(kv_bits, ctypes.c_uint16),
+                                       kv_bits.shape[1] * d_qk, _ptr(seqlens, ctypes.c_int32),
+                                       batch, q_len, heads, d_qk, d_v, int(dtype), float(scale),
+                                       _ptr(out, ctypes.c_double), _ptr(lse, ctypes.c_double), int(nthreads))
+    if rc != 0:
+        raise RuntimeError("mla_oracle_decode_general failed")
     return out, lse
 
 

@@ -72,13 +72,14 @@ constexpr int kVAhead = 6;                     // value tiles of V^T reads in fl
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef short i16x4 __attribute__((ext_vector_type(4)));
 typedef __attribute__((address_space(3))) char lds_char;
 
 struct Params {
-    const char *q;            // bf16 [batch][16][576]
-    const char *kv;           // bf16 rows of 576
+    const char *q;            // 16-bit floats [batch][16][576]
+    const char *kv;           // 16-bit float rows of 576
     long long kv_batch_bytes; // bytes between sequences
     const int *seqlens;       // [batch]
     float *out;               // [batch][16][512]
@@ -169,6 +170,15 @@ __device__ __forceinline__ void bound_workgroups(int seq_first, int ub, int tota
     last = (int)((((long long)seq_first + ub) * G + U - 1) / U) - 1;
 }
 
+// One 16x16x32 matrix-core step on 16-bit operands held as raw bits; kDtype selects bf16 or fp16.
+template <int kDtype>
+__device__ __forceinline__ f32x4 mfma_16x16x32(u32x4 a, u32x4 b, f32x4 c) {
+    if constexpr (kDtype == MLA_DTYPE_BF16)
+        return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
+    else
+        return __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(f16x8, a), __builtin_bit_cast(f16x8, b), c, 0, 0, 0);
+}
+
 constexpr float kLazyLog2 = 8.0f;   // the softmax reference moves only when exceeded by 2^8
 
 // O <- O * alpha with O resident in accumulation registers (AGPRs), which the vector ALU cannot
@@ -190,6 +200,7 @@ __device__ __forceinline__ void rescale_accumulators(f32x4 (&o)[kDvTiles], float
 
 // Main kernel (steps a0-a7 of the hot path): persistent grid, workgroup k streams its share of
 // the unit stream segment by segment.
+template <int kDtype>
 __global__ void __launch_bounds__(kThreads, 1) mla_decode_split_kernel(const Params p) {
     extern __shared__ __attribute__((aligned(16))) char smem[];
 
@@ -261,11 +272,11 @@ __global__ void __launch_bounds__(kThreads, 1) mla_decode_split_kernel(const Par
             }
         };
         // ---- a1: Q^T as the MFMA B operand: lane (head r16, k-group g) holds dims 32*kk + 8*g .. +8
-        bf16x8 qf[kKSteps];
+        u32x4 qf[kKSteps];
         {
             const u32x4 *qp = reinterpret_cast<const u32x4 *>(p.q + ((long long)b * kHeads + r16) * kRowBytes) + g;
 #pragma unroll
-            for (int kk = 0; kk < kKSteps; ++kk) qf[kk] = __builtin_bit_cast(bf16x8, qp[4 * kk]);
+            for (int kk = 0; kk < kKSteps; ++kk) qf[kk] = qp[4 * kk];
         }
 
         // this wavefront's tiles of the segment: w, w + 4, w + 8, ...
@@ -309,14 +320,14 @@ __global__ void __launch_bounds__(kThreads, 1) mla_decode_split_kernel(const Par
                 }
 #pragma unroll
                 for (int kk = 0; kk < kKSteps; ++kk) {
-                    const bf16x8 k0 = __builtin_bit_cast(bf16x8, kb[kk % kKAhead][0]);
-                    const bf16x8 k1 = __builtin_bit_cast(bf16x8, kb[kk % kKAhead][1]);
+                    const u32x4 k0 = kb[kk % kKAhead][0];
+                    const u32x4 k1 = kb[kk % kKAhead][1];
                     if (kk + kKAhead < kKSteps) {
                         kb[kk % kKAhead][0] = *reinterpret_cast<const u32x4 *>(rd_k + (kk + kKAhead) * 64);
                         kb[kk % kKAhead][1] = *reinterpret_cast<const u32x4 *>(rd_k + 16 * kLdsRow + (kk + kKAhead) * 64);
                     }
-                    s0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(k0, qf[kk], s0, 0, 0, 0);
-                    s1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(k1, qf[kk], s1, 0, 0, 0);
+                    s0 = mfma_16x16x32<kDtype>(k0, qf[kk], s0);
+                    s1 = mfma_16x16x32<kDtype>(k1, qf[kk], s1);
                 }
                 // pin that interleaving for the instruction scheduler: reads first, then
                 // (2 MFMA, 2 LDS reads) per k-step, so LDS latency hides behind the MFMAs
@@ -364,13 +375,26 @@ __global__ void __launch_bounds__(kThreads, 1) mla_decode_split_kernel(const Par
                 l_run += pr[i];
             }
 
-            // P^T as B operand, two-term bf16 split
-            bf16x8 p_hi, p_lo;
+            // P^T as B operand.  bf16: two-term split hi + lo (16 significant bits); fp16: one term
+            // (11 significant bits; p <= 2^8 is far inside the fp16 range).
+            u32x4 p_hi, p_lo;
+            if constexpr (kDtype == MLA_DTYPE_BF16) {
+                bf16x8 hi, lo;
 #pragma unroll
-            for (int i = 0; i < 8; ++i) {
-                p_hi[i] = (__bf16)pr[i];
-                p_lo[i] = (__bf16)(pr[i] - (float)p_hi[i]);
+                for (int i = 0; i < 8; ++i) {
+                    hi[i] = (__bf16)pr[i];
+                    lo[i] = (__bf16)(pr[i] - (float)hi[i]);
+                }
+                p_hi = __builtin_bit_cast(u32x4, hi);
+                p_lo = __builtin_bit_cast(u32x4, lo);
+            } else {
+                f16x8 hi;
+#pragma unroll
+                for (int i = 0; i < 8; ++i) hi[i] = (_Float16)pr[i];
+                p_hi = __builtin_bit_cast(u32x4, hi);
+                p_lo = p_hi;    // unused
             }
+            constexpr int kPTerms = (kDtype == MLA_DTYPE_BF16) ? 2 : 1;
 
             // ---- a6: O^T += V^T P^T (equation (3)), V^T from the same LDS tile --------------
             // The transposing reads run kVAhead value tiles ahead of their MFMAs.
@@ -384,19 +408,19 @@ __global__ void __launch_bounds__(kThreads, 1) mla_decode_split_kernel(const Par
 #pragma unroll
                 for (int ct = 0; ct < kDvTiles; ++ct) {
                     const i16x4 vv[2] = {vb[ct % kVAhead][0], vb[ct % kVAhead][1]};
-                    bf16x8 vt;
+                    u32x4 vt;
                     __builtin_memcpy(&vt, vv, 16);
                     if (ct + kVAhead < kDvTiles) {
                         vb[ct % kVAhead][0] = read_tr16(rd_v + (ct + kVAhead) * 32);
                         vb[ct % kVAhead][1] = read_tr16(rd_v + 16 * kLdsRow + (ct + kVAhead) * 32);
                     }
-                    o[ct] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vt, p_hi, o[ct], 0, 0, 0);
-                    o[ct] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vt, p_lo, o[ct], 0, 0, 0);
+                    o[ct] = mfma_16x16x32<kDtype>(vt, p_hi, o[ct]);
+                    if constexpr (kPTerms == 2) o[ct] = mfma_16x16x32<kDtype>(vt, p_lo, o[ct]);
                 }
                 __builtin_amdgcn_sched_group_barrier(kSchedDsRead, 2 * kVAhead, 1);
 #pragma unroll
                 for (int ct = 0; ct < kDvTiles; ++ct) {
-                    __builtin_amdgcn_sched_group_barrier(kSchedMfma, 2, 1);
+                    __builtin_amdgcn_sched_group_barrier(kSchedMfma, kPTerms, 1);
                     if (ct + kVAhead < kDvTiles) __builtin_amdgcn_sched_group_barrier(kSchedDsRead, 2, 1);
                 }
             }
@@ -554,22 +578,24 @@ mla_status_t validate(const void *q, const void *kv_cache, int64_t kv_batch_stri
 mla_status_t launch(const void *q, const void *kv_cache, int64_t kv_batch_stride,
                     const int32_t *cache_seqlens, int batch, int max_seqlen_kv, float scale,
                     float *out, float *lse, void *workspace, size_t workspace_bytes, int num_wg,
-                    int flags, void *stream) {
+                    int flags, int dtype, void *stream) {
     if (num_wg <= 0 || num_wg > kMaxWorkgroups) return MLA_ERR_INVALID_ARG;
     if (workspace_bytes < workspace_bytes_for(batch, num_wg)) return MLA_ERR_WORKSPACE_TOO_SMALL;
 
     // the main kernel needs more dynamic LDS than the default limit: raise it once per device
     static std::mutex mu;
-    static bool attr_done[64] = {};
+    static bool attr_done[64][2] = {};
     int dev = 0;
     if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return MLA_ERR_HIP;
+    const void *split_fn = dtype == MLA_DTYPE_F16
+                               ? reinterpret_cast<const void *>(mla_decode_split_kernel<MLA_DTYPE_F16>)
+                               : reinterpret_cast<const void *>(mla_decode_split_kernel<MLA_DTYPE_BF16>);
     {
         std::lock_guard<std::mutex> lock(mu);
-        if (!attr_done[dev]) {
-            if (hipFuncSetAttribute(reinterpret_cast<const void *>(mla_decode_split_kernel),
-                                    hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes) != hipSuccess)
+        if (!attr_done[dev][dtype]) {
+            if (hipFuncSetAttribute(split_fn, hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes) != hipSuccess)
                 return MLA_ERR_HIP;
-            attr_done[dev] = true;
+            attr_done[dev][dtype] = true;
         }
     }
 
@@ -589,7 +615,10 @@ mla_status_t launch(const void *q, const void *kv_cache, int64_t kv_batch_stride
 
     hipStream_t hs = static_cast<hipStream_t>(stream);
     if (flags & MLA_PHASE_SPLIT) {
-        hipLaunchKernelGGL(mla_decode_split_kernel, dim3(num_wg), dim3(kThreads), kLdsBytes, hs, p);
+        if (dtype == MLA_DTYPE_F16)
+            hipLaunchKernelGGL(mla_decode_split_kernel<MLA_DTYPE_F16>, dim3(num_wg), dim3(kThreads), kLdsBytes, hs, p);
+        else
+            hipLaunchKernelGGL(mla_decode_split_kernel<MLA_DTYPE_BF16>, dim3(num_wg), dim3(kThreads), kLdsBytes, hs, p);
         if (hipGetLastError() != hipSuccess) return MLA_ERR_HIP;
     }
     if (flags & MLA_PHASE_COMBINE) {
@@ -632,10 +661,11 @@ mla_status_t mla_decode_workspace_size(int batch, int num_heads, int max_seqlen_
     return MLA_OK;
 }
 
-mla_status_t mla_decode_ex(const void *q, const void *kv_cache, int64_t kv_batch_stride,
-                           const int32_t *cache_seqlens, int batch, int num_heads, int max_seqlen_kv,
-                           float scale, float *out, float *lse, void *workspace, size_t workspace_bytes,
-                           int num_workgroups, int flags, void *stream) {
+mla_status_t mla_decode_typed(const void *q, const void *kv_cache, int64_t kv_batch_stride,
+                              const int32_t *cache_seqlens, int batch, int num_heads, int max_seqlen_kv,
+                              int dtype, float scale, float *out, float *lse, void *workspace,
+                              size_t workspace_bytes, int num_workgroups, int flags, void *stream) {
+    if (dtype != MLA_DTYPE_BF16 && dtype != MLA_DTYPE_F16) return MLA_ERR_INVALID_ARG;
     mla_status_t st = validate(q, kv_cache, kv_batch_stride, cache_seqlens, batch, num_heads, max_seqlen_kv,
                                scale, out, lse, workspace);
     if (st != MLA_OK) return st;
@@ -647,7 +677,16 @@ mla_status_t mla_decode_ex(const void *q, const void *kv_cache, int64_t kv_batch
         if (st != MLA_OK) return st;
     }
     return launch(q, kv_cache, kv_batch_stride, cache_seqlens, batch, max_seqlen_kv, scale, out, lse,
-                  workspace, workspace_bytes, num_workgroups, flags, stream);
+                  workspace, workspace_bytes, num_workgroups, flags, dtype, stream);
+}
+
+mla_status_t mla_decode_ex(const void *q, const void *kv_cache, int64_t kv_batch_stride,
+                           const int32_t *cache_seqlens, int batch, int num_heads, int max_seqlen_kv,
+                           float scale, float *out, float *lse, void *workspace, size_t workspace_bytes,
+                           int num_workgroups, int flags, void *stream) {
+    return mla_decode_typed(q, kv_cache, kv_batch_stride, cache_seqlens, batch, num_heads, max_seqlen_kv,
+                            MLA_DTYPE_BF16, scale, out, lse, workspace, workspace_bytes, num_workgroups, flags,
+                            stream);
 }
 
 mla_status_t mla_decode(const void *q, const void *kv_cache, int64_t kv_batch_stride,

@@ -36,34 +36,42 @@ def bf16_bits(t: torch.Tensor) -> np.ndarray:
     return t.contiguous().view(torch.int16).numpy().view(np.uint16)
 
 
+def bits16(t: torch.Tensor) -> np.ndarray:
+    """bf16 or fp16 CPU tensor -> numpy uint16 array of its bit patterns."""
+    if t.dtype not in (torch.bfloat16, torch.float16) or t.device.type != "cpu":
+        raise TypeError("expected a CPU bf16 or fp16 tensor")
+    return t.contiguous().view(torch.int16).numpy().view(np.uint16)
+
+
 def make_inputs(batch, max_seqlen, seqlens=None, seed=BASE_SEED, heads=NUM_HEADS, d_qk=D_QK,
-                poison_tail=False):
-    """Draw q [batch, 1, heads, d_qk] and kv [batch, max_seqlen, d_qk] ~ N(0,1), rounded to bf16.
+                poison_tail=False, dtype=torch.bfloat16, q_len=1):
+    """Draw q [batch, q_len, heads, d_qk] and kv [batch, max_seqlen, d_qk] ~ N(0,1), rounded to
+    ``dtype`` (bf16 by default, or fp16).
 
     seqlens: None (every sequence is max_seqlen long) or an int sequence of length batch.
     Rows at or beyond a sequence's length are zero, or NaN when poison_tail is set
     (a correct kernel never lets them reach the result).
-    Returns CPU tensors (q bf16, kv bf16, seqlens int32).
+    Returns CPU tensors (q, kv in ``dtype``, seqlens int32).
     """
     g = torch.Generator().manual_seed(int(seed))
-    q = torch.randn((batch, 1, heads, d_qk), generator=g, dtype=torch.float32).to(torch.bfloat16)
+    q = torch.randn((batch, q_len, heads, d_qk), generator=g, dtype=torch.float32).to(dtype)
     if seqlens is None:
         lens = torch.full((batch,), max_seqlen, dtype=torch.int32)
     else:
         lens = torch.as_tensor(list(seqlens), dtype=torch.int32)
         if lens.shape != (batch,) or int(lens.min()) < 0 or int(lens.max()) > max_seqlen:
             raise ValueError("seqlens must have one entry in [0, max_seqlen] per sequence")
-    kv = torch.empty((batch, max_seqlen, d_qk), dtype=torch.bfloat16)
+    kv = torch.empty((batch, max_seqlen, d_qk), dtype=dtype)
     for b in range(batch):
         n = int(lens[b])
         if n > 0:
-            kv[b, :n] = torch.randn((n, d_qk), generator=g, dtype=torch.float32).to(torch.bfloat16)
+            kv[b, :n] = torch.randn((n, d_qk), generator=g, dtype=torch.float32).to(dtype)
         if n < max_seqlen:
             kv[b, n:] = float("nan") if poison_tail else 0.0
     return q, kv, lens
 
 
-def make_config(cfg_id, poison_tail=False):
+def make_config(cfg_id, poison_tail=False, dtype=torch.bfloat16):
     """Inputs of one of the five benchmark configurations (seed = BASE_SEED + cfg_id)."""
     c = CONFIGS[cfg_id]
     seed = BASE_SEED + cfg_id
@@ -72,7 +80,7 @@ def make_config(cfg_id, poison_tail=False):
         lo, hi = c["ragged"]
         gl = torch.Generator().manual_seed(seed + 1000)
         seqlens = torch.randint(lo, hi + 1, (c["batch"],), generator=gl).tolist()
-    return make_inputs(c["batch"], c["seqlen"], seqlens, seed=seed, poison_tail=poison_tail)
+    return make_inputs(c["batch"], c["seqlen"], seqlens, seed=seed, poison_tail=poison_tail, dtype=dtype)
 
 
 def algorithmic_bytes(seqlens, heads=NUM_HEADS, d_qk=D_QK, d_v=D_V) -> int:

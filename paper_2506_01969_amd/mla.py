@@ -49,6 +49,9 @@ def lib():
         L.mla_decode_ex.argtypes = [vp, vp, ctypes.c_int64, vp, ci, ci, ci, ctypes.c_float, vp, vp,
                                     vp, sz, ci, ci, vp]
         L.mla_decode_ex.restype = ci
+        L.mla_decode_typed.argtypes = [vp, vp, ctypes.c_int64, vp, ci, ci, ci, ci, ctypes.c_float, vp, vp,
+                                       vp, sz, ci, ci, vp]
+        L.mla_decode_typed.restype = ci
         L.mla_status_string.argtypes = [ci]
         L.mla_status_string.restype = ctypes.c_char_p
         _lib = L
@@ -66,8 +69,8 @@ def mla_decode_workspace_size(batch, num_heads, max_seqlen_kv, num_workgroups=0)
 
 
 def _check_tensors(q, kv_cache, cache_seqlens):
-    if q.dtype != torch.bfloat16 or kv_cache.dtype != torch.bfloat16:
-        raise TypeError("q and kv_cache must be bf16")
+    if q.dtype not in (torch.bfloat16, torch.float16) or kv_cache.dtype != q.dtype:
+        raise TypeError("q and kv_cache must both be bf16 or both be fp16")
     if cache_seqlens.dtype != torch.int32:
         raise TypeError("cache_seqlens must be int32")
     if not (q.is_cuda and kv_cache.is_cuda and cache_seqlens.is_cuda):
@@ -84,13 +87,16 @@ def _check_tensors(q, kv_cache, cache_seqlens):
 
 PHASE_SPLIT = 1
 PHASE_COMBINE = 2
+DTYPE_BF16 = 0
+DTYPE_F16 = 1
 
 
 def mla_decode(q, kv_cache, cache_seqlens, scale, out=None, lse=None, workspace=None, num_workgroups=None,
                phases=None):
     """out [batch, 1, heads, 512] fp32, lse [batch, heads] fp32 on the current stream (asynchronous).
 
-    q [batch, 1, 16, 576] bf16, kv_cache [batch, max_seqlen_kv, 576] bf16 (batch stride free),
+    q [batch, 1, 16, 576] and kv_cache [batch, max_seqlen_kv, 576] (batch stride free), both bf16
+    or both fp16 (fp16 goes through ``mla_decode_typed``),
     cache_seqlens [batch] int32, all on the current device.  ``out``, ``lse`` and ``workspace``
     (a uint8 tensor) are allocated with torch when not given.  ``num_workgroups`` forces the
     split plan and ``phases`` selects the kernels (both go through ``mla_decode_ex``).
@@ -107,11 +113,16 @@ def mla_decode(q, kv_cache, cache_seqlens, scale, out=None, lse=None, workspace=
     if workspace is None:
         workspace = torch.empty((need,), dtype=torch.uint8, device=dev)
     stream = ctypes.c_void_p(torch.cuda.current_stream(dev).cuda_stream)
-    args = [ctypes.c_void_p(q.data_ptr()), ctypes.c_void_p(kv_cache.data_ptr()), kv_cache.stride(0),
-            ctypes.c_void_p(cache_seqlens.data_ptr()), batch, heads, max_seqlen, float(scale),
-            ctypes.c_void_p(out.data_ptr()), ctypes.c_void_p(lse.data_ptr()),
+    head = [ctypes.c_void_p(q.data_ptr()), ctypes.c_void_p(kv_cache.data_ptr()), kv_cache.stride(0),
+            ctypes.c_void_p(cache_seqlens.data_ptr()), batch, heads, max_seqlen]
+    tail = [float(scale), ctypes.c_void_p(out.data_ptr()), ctypes.c_void_p(lse.data_ptr()),
             ctypes.c_void_p(workspace.data_ptr()), workspace.numel() * workspace.element_size()]
-    if num_workgroups is None and phases is None:
+    args = head + tail
+    if q.dtype == torch.float16:
+        st = lib().mla_decode_typed(*head, DTYPE_F16, *tail, int(num_workgroups or 0),
+                                    int(PHASE_SPLIT | PHASE_COMBINE if phases is None else phases), stream)
+        where = "mla_decode_typed"
+    elif num_workgroups is None and phases is None:
         st = lib().mla_decode(*args, stream)
         where = "mla_decode"
     else:

@@ -192,3 +192,45 @@ def test_benchmark_configs_full_parity(oracle, cfg):
     print("case config", cfg, "oracle", flush=True)
     ref_o, ref_l = _oracle(oracle, q, kv, l)
     _check(out, lse, ref_o, ref_l, label="config %d" % cfg)
+
+
+# ---- fp16 inputs (the paper's own precision, Section 4.1) through mla_decode_typed ------------------
+# One fp16 term of P: up to 2^-12 relative error per term.  When a single token dominates (very
+# short sequences) the output error is that times |v| <= 4.5: max-abs <= 1.1e-3.  Averaged over a
+# case the error model in tests/test_oracle.py gives RMSE 2e-5 at KV 512 and less at longer KV.
+
+F16_MAX_ABS, F16_RMSE, F16_LSE = 1.2e-3, 4e-5, 2e-5
+
+
+def _oracle_f16(oracle, q, kv, lens, scale=inputs.SCALE):
+    o, l = oracle.decode_general(inputs.bits16(q), inputs.bits16(kv), lens.numpy(), scale, inputs.D_V, dtype=oracle.F16)
+    return o[:, 0], l[:, 0]
+
+
+def _check_f16(out, lse, ref_o, ref_l, label):
+    _check(out, lse, ref_o, ref_l, tight=False, label=label)
+    err = np.abs(out - ref_o)
+    fin = np.isfinite(ref_l)
+    assert err.max() <= F16_MAX_ABS and math.sqrt(float((err ** 2).mean())) <= F16_RMSE, label
+    assert not fin.any() or np.abs(lse[fin] - ref_l[fin]).max() <= F16_LSE, label
+
+
+@pytest.mark.parametrize("num_wg", [None, 1, 7, 1000])
+def test_fp16_small_ragged_elementwise(oracle, num_wg):
+    lens = [1, 31, 32, 33, 127, 128, 129, 700, 1000, 0, 513, 640]
+    q, kv, l = inputs.make_inputs(len(lens), 1000, lens, seed=201, poison_tail=True, dtype=torch.float16)
+    ref_o, ref_l = _oracle_f16(oracle, q, kv, l)
+    print("case fp16 small_ragged num_wg", num_wg, flush=True)
+    out, lse = _run(q, kv, l, num_wg=num_wg)
+    _check_f16(out, lse, ref_o, ref_l, "fp16 small_ragged num_wg=%s" % num_wg)
+
+
+@pytest.mark.parametrize("cfg", [1, 2, 4, 5])
+def test_fp16_benchmark_configs_full_parity(oracle, cfg):
+    print("case fp16 config", cfg, "generating", flush=True)
+    q, kv, l = inputs.make_config(cfg, poison_tail=True, dtype=torch.float16)
+    print("case fp16 config", cfg, "gpu", flush=True)
+    out, lse = _run(q, kv, l)
+    print("case fp16 config", cfg, "oracle", flush=True)
+    ref_o, ref_l = _oracle_f16(oracle, q, kv, l)
+    _check_f16(out, lse, ref_o, ref_l, "fp16 config %d" % cfg)

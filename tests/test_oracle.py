@@ -288,3 +288,90 @@ def test_error_model_of_bf16_probabilities(oracle):
     assert rmse2 < 2e-6          # hi + lo: two orders inside the bound
     assert np.abs(o2 - ref_o[0]).max() < 2e-5
     assert np.abs(l2 - ref_l[0]).max() < 1e-5
+
+
+# ---- 9. the general entry: fp16 bit patterns and more than one query token --------------------
+
+def test_fp16_decode_of_every_finite_bit_pattern(oracle):
+    """d_qk = d_v = 1, one token, q = 1: out is the decoded KV element itself.  Every finite fp16
+    bit pattern (normals, subnormals, both zeros) must decode to numpy's float16 value."""
+    bits = np.arange(65536, dtype=np.uint32).astype(np.uint16)
+    vals = bits.view(np.float16).astype(np.float64)
+    keep = np.isfinite(vals)
+    bits, vals = bits[keep], vals[keep]
+    n = bits.size
+    q = np.full((n, 1, 1, 1), np.float16(1.0).view(np.uint16), dtype=np.uint16)
+    kv = bits.reshape(n, 1, 1)
+    out, lse = oracle.decode_general(q, kv, np.ones(n, dtype=np.int32), 0.5, 1, dtype=oracle.F16)
+    np.testing.assert_array_equal(out.reshape(n), vals)          # exact, including signed zeros' value
+    np.testing.assert_allclose(lse.reshape(n), 0.5 * vals, rtol=0, atol=0)
+
+
+def test_general_with_bf16_and_one_query_token_is_the_plain_oracle(oracle):
+    qb, kvb, lens = _small(3, 40, 4, 16, seed=51, seqlens=[40, 7, 0])
+    o1, l1 = oracle.decode(qb, kvb, lens, 0.3, 12)
+    o2, l2 = oracle.decode_general(qb, kvb, lens, 0.3, 12, dtype=oracle.BF16)
+    np.testing.assert_array_equal(o1, o2[:, 0])
+    np.testing.assert_array_equal(l1, l2[:, 0])
+
+
+def test_fp16_against_numpy_float64(oracle):
+    q, kv, lens = inputs.make_inputs(2, 300, [300, 77], seed=52, dtype=torch.float16)
+    qb, kvb = inputs.bits16(q), inputs.bits16(kv)
+    out, lse = oracle.decode_general(qb, kvb, lens.numpy(), inputs.SCALE, inputs.D_V, dtype=oracle.F16)
+    for b in range(2):
+        n = int(lens[b])
+        qd = qb[b, 0].view(np.float16).astype(np.float64)          # numpy's own fp16 decode
+        kd = kvb[b, :n].view(np.float16).astype(np.float64)
+        s = (qd @ kd.T) * inputs.SCALE
+        e = np.exp(s)
+        np.testing.assert_allclose(out[b, 0], (e / e.sum(-1, keepdims=True)) @ kd[:, :inputs.D_V], rtol=0, atol=1e-13)
+        np.testing.assert_allclose(lse[b, 0], np.log(e.sum(-1)), rtol=0, atol=1e-12)
+    # the same bits read as bf16 give a different answer: the type argument is honoured
+    out_b, _ = oracle.decode_general(qb, kvb, lens.numpy(), inputs.SCALE, inputs.D_V, dtype=oracle.BF16)
+    assert np.abs(out_b - out).max() > 1e-3
+
+
+def test_two_query_tokens_are_causal_among_themselves(oracle):
+    """Query token j of q_len sees KV rows [0, N - (q_len - 1 - j)).  Checked against a dense
+    float64 softmax with the mask written out as a matrix, for q_len 2 and 3."""
+    for q_len in (2, 3):
+        lens = [50, 3, q_len, 1]
+        q, kv, l = inputs.make_inputs(4, 50, lens, seed=53 + q_len, heads=5, d_qk=24, q_len=q_len)
+        qb, kvb = inputs.bf16_bits(q), inputs.bf16_bits(kv)
+        out, lse = oracle.decode_general(qb, kvb, l.numpy(), 0.21, 20)
+        for b in range(4):
+            n = lens[b]
+            kd = _decode_bf16(kvb)[b, :n]
+            for j in range(q_len):
+                vis = n - (q_len - 1 - j)
+                mask = np.arange(n) < vis                         # [n]
+                s = (_decode_bf16(qb)[b, j] @ kd.T) * 0.21        # [heads, n]
+                if vis <= 0:
+                    assert (out[b, j] == 0).all() and np.isneginf(lse[b, j]).all()
+                    continue
+                e = np.where(mask[None, :], np.exp(s), 0.0)
+                np.testing.assert_allclose(out[b, j], (e / e.sum(-1, keepdims=True)) @ kd[:, :20], rtol=0, atol=1e-13)
+                np.testing.assert_allclose(lse[b, j], np.log(e.sum(-1)), rtol=0, atol=1e-12)
+        # the last query token is the plain one-token oracle on that query slice
+        o1, l1 = oracle.decode(np.ascontiguousarray(qb[:, q_len - 1:q_len]), kvb, l.numpy(), 0.21, 20)
+        np.testing.assert_array_equal(o1, out[:, q_len - 1])
+        np.testing.assert_array_equal(l1, lse[:, q_len - 1])
+
+
+def test_error_model_of_fp16_probabilities(oracle):
+    """fp16 inputs: one fp16 rounding of P (11 significant bits) is inside the 1e-4 RMSE bound
+    even at the shortest KV length, so the fp16 kernel needs no second term."""
+    q, kv, lens = inputs.make_config(1, dtype=torch.float16)
+    ref_o, ref_l = oracle.decode_general(inputs.bits16(q), inputs.bits16(kv), lens.numpy(), inputs.SCALE,
+                                         inputs.D_V, dtype=oracle.F16)
+    qf = q[0, 0].float(); kf = kv[0, :512].float()
+    s = (qf.double() @ kf.double().T).float() * np.float32(inputs.SCALE)
+    m = s.max(dim=-1, keepdim=True).values
+    p = torch.exp(s - m)
+    l = p.sum(-1, keepdim=True)
+    acc = p.to(torch.float16).double() @ kf[:, :inputs.D_V].double()
+    o = (acc / l.double()).numpy()
+    rmse = math.sqrt(((o - ref_o[0, 0]) ** 2).mean())
+    assert rmse < 4e-5
+    assert np.abs(o - ref_o[0, 0]).max() < 2e-4
