@@ -72,6 +72,8 @@ def main():
     ap.add_argument("--config", type=int, default=4, help="benchmark configuration id (4 = headline)")
     ap.add_argument("--workgroups", type=int, default=0, help="force the number of workgroups (0 = automatic)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--q-len", type=int, default=1,
+                    help="query tokens per sequence (1 = the headline metric; the paper names 1 or 2)")
     ap.add_argument("--dtype", choices=("bf16", "fp16"), default="bf16",
                     help="element type of q and the KV cache (bf16 = the headline metric; fp16 = the paper's own)")
     ap.add_argument("--sweep", action="store_true",
@@ -112,7 +114,7 @@ def main():
 
     cfg = inputs.CONFIGS[args.config]
     dt = torch.float16 if args.dtype == "fp16" else torch.bfloat16
-    q, kv, lens = inputs.make_config(args.config, dtype=dt)
+    q, kv, lens = inputs.make_config(args.config, dtype=dt, q_len=args.q_len)
     batch, max_seqlen = cfg["batch"], cfg["seqlen"]
     alg_bytes = inputs.algorithmic_bytes(lens.tolist())
     alg_flops = inputs.algorithmic_flops(lens.tolist())
@@ -125,10 +127,13 @@ def main():
     for _ in range(n_buf - 1):
         kvs.append(kvs[0].clone())
     nwg = args.workgroups or None
-    need, nwg_used = mla.mla_decode_workspace_size(batch, 16, max_seqlen, args.workgroups)
+    need, nwg_used = mla.mla_decode_workspace_size(batch * args.q_len, 16, max_seqlen, args.workgroups)
     ws = torch.empty((need,), dtype=torch.uint8, device=dev)
-    out = torch.empty((batch, 1, 16, 512), dtype=torch.float32, device=dev)
-    lse = torch.empty((batch, 16), dtype=torch.float32, device=dev)
+    out = torch.empty((batch, args.q_len, 16, 512), dtype=torch.float32, device=dev)
+    lse = torch.empty((batch, args.q_len, 16), dtype=torch.float32, device=dev)
+    # q, out and lse of the extra query tokens are algorithmic bytes too; the KV rows are still read once
+    alg_bytes += (args.q_len - 1) * batch * (16 * 576 * 2 + 16 * 512 * 4 + 16 * 4)
+    alg_flops *= args.q_len
 
     def step(i, phases=None):
         mla.mla_decode(qd, kvs[i % n_buf], ld, inputs.SCALE, out=out, lse=lse, workspace=ws,
@@ -186,11 +191,11 @@ def main():
         t0 = time.perf_counter()
         ref_o, ref_l = mla_oracle.decode_general(qb, kvb, ls.numpy(), inputs.SCALE, inputs.D_V,
                                                  dtype=mla_oracle.F16 if args.dtype == "fp16" else mla_oracle.BF16)
-        ref_o = ref_o[:, 0]
+        ref_o = ref_o.reshape(ns, args.q_len * 16, 512)
         cpu_s = time.perf_counter() - t0
         sample_bytes = inputs.algorithmic_bytes(ls.tolist())
         # the same sample doubles as a sanity check of the benchmarked output
-        got = out.cpu().numpy().reshape(batch, 16, 512)[:ns]
+        got = out.cpu().numpy().reshape(batch, args.q_len * 16, 512)[:ns]
         max_abs = float(abs(got - ref_o).max())
         cpu = {"value": sample_bytes / cpu_s / 1e12, "unit": "TB/s", "cores": mla_oracle.threads(), "kind": "oracle",
                "sample": "first %d of %d sequences, all 16 heads, full KV (%d tokens), one oracle call" % (
@@ -202,9 +207,9 @@ def main():
         "metric": METRIC, "value": tbps, "unit": "TB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_per_step, "us_per_call": ms_per_step * 1e3, "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": args.dtype, "data": "synthetic",
-        "config": {"workload": "config %d: MLA decode batch %d, q_len 1, 16 heads, shared 576-d %s latent KV, "
+        "config": {"workload": "config %d: MLA decode batch %d, q_len %d, 16 heads, shared 576-d %s latent KV, "
                                "KV length %s, scale 1/sqrt(192), d_v 512" % (
-                                   args.config, batch, args.dtype, "%d per sequence" % max_seqlen if cfg["ragged"] is None
+                                   args.config, batch, args.q_len, args.dtype, "%d per sequence" % max_seqlen if cfg["ragged"] is None
                                    else "ragged uniform[%d,%d]" % cfg["ragged"]),
                    "total_kv_tokens": int(lens.sum()), "algorithmic_bytes_per_call": alg_bytes,
                    "algorithmic_flops_per_call": alg_flops, "workgroups": nwg_used,

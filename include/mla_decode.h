@@ -62,7 +62,9 @@ typedef enum {
  *   max_seqlen_kv        >= 1, rows allocated per sequence in the KV cache
  *   num_workgroups       workgroups the KV stream is divided over; 0 = automatic
  *   bytes                [out, host] workspace size the call needs
- *   num_workgroups_used  [out, host, may be NULL] the number the size was computed for
+ *   num_workgroups_used  [out, host, may be NULL] num_workgroups, or for 0 the automatic plan
+ *                        for one query token per sequence (with more, see mla_decode_typed(),
+ *                        the plan is every compute unit, and the size returned for 0 covers it)
  */
 mla_status_t mla_decode_workspace_size(int batch, int num_heads, int max_seqlen_kv,
                                        int num_workgroups, size_t *bytes,
@@ -118,17 +120,32 @@ mla_status_t mla_decode_ex(const void *q, const void *kv_cache, int64_t kv_batch
                            int flags, void *stream);
 
 /*
- * The same call for either 16-bit input type.  The paper's own runs are FP16 (Section 4.1);
- * the matrix-core products then take fp16 operands, and the softmax probabilities enter the
- * second product as ONE fp16 term (11 significant bits) instead of the two-term bf16 split.
+ * The general call: either 16-bit input type, and one or more query tokens per sequence.
+ *
  *   dtype  MLA_DTYPE_BF16 or MLA_DTYPE_F16: the element type of q and kv_cache (out and lse
- *          stay fp32); any other value is MLA_ERR_INVALID_ARG.
+ *          stay fp32); any other value is MLA_ERR_INVALID_ARG.  The paper's own runs are FP16
+ *          (Section 4.1); the matrix-core products then take fp16 operands, and the softmax
+ *          probabilities enter the second product as ONE fp16 term (11 significant bits)
+ *          instead of the two-term bf16 split.
+ *   q_len  query tokens per sequence, 1 .. MLA_MAX_Q_LEN (Section 3.1: decoding feeds one or
+ *          two tokens per step); other values are MLA_ERR_UNSUPPORTED_SHAPE.  Then
+ *            q    is [batch][q_len][16][576],
+ *            out  is [batch][q_len][16][512],  lse is [batch][q_len][16],
+ *            cache_seqlens[b] counts the KV rows INCLUDING those of the q_len new tokens, which
+ *            are the last q_len rows of the sequence, and attention is causal among them: query
+ *            token j (0-based) attends to rows [0, cache_seqlens[b] - (q_len - 1 - j)); a token
+ *            left with no row yields out = 0 and lse = -inf.
+ *          The workspace must have the size mla_decode_workspace_size() returns for
+ *          batch * q_len in place of batch.  The workgroups run in teams of q_len that take the
+ *          same KV rows at the same time, one query token each, so a row comes in from HBM once
+ *          and the other readers are served by the memory-side cache.
  * All other arguments, layouts and error behaviour are those of mla_decode_ex().
  */
 #define MLA_DTYPE_BF16 0
 #define MLA_DTYPE_F16 1
+#define MLA_MAX_Q_LEN 8
 mla_status_t mla_decode_typed(const void *q, const void *kv_cache, int64_t kv_batch_stride,
-                              const int32_t *cache_seqlens, int batch, int num_heads,
+                              const int32_t *cache_seqlens, int batch, int q_len, int num_heads,
                               int max_seqlen_kv, int dtype, float scale, float *out, float *lse,
                               void *workspace, size_t workspace_bytes, int num_workgroups,
                               int flags, void *stream);

@@ -71,7 +71,7 @@ def make_inputs(batch, max_seqlen, seqlens=None, seed=BASE_SEED, heads=NUM_HEADS
     return q, kv, lens
 
 
-def make_config(cfg_id, poison_tail=False, dtype=torch.bfloat16):
+def make_config(cfg_id, poison_tail=False, dtype=torch.bfloat16, q_len=1):
     """Inputs of one of the five benchmark configurations (seed = BASE_SEED + cfg_id)."""
     c = CONFIGS[cfg_id]
     seed = BASE_SEED + cfg_id
@@ -80,7 +80,7 @@ def make_config(cfg_id, poison_tail=False, dtype=torch.bfloat16):
         lo, hi = c["ragged"]
         gl = torch.Generator().manual_seed(seed + 1000)
         seqlens = torch.randint(lo, hi + 1, (c["batch"],), generator=gl).tolist()
-    return make_inputs(c["batch"], c["seqlen"], seqlens, seed=seed, poison_tail=poison_tail, dtype=dtype)
+    return make_inputs(c["batch"], c["seqlen"], seqlens, seed=seed, poison_tail=poison_tail, dtype=dtype, q_len=q_len)
 
 
 def algorithmic_bytes(seqlens, heads=NUM_HEADS, d_qk=D_QK, d_v=D_V) -> int:

@@ -49,7 +49,7 @@ def lib():
         L.mla_decode_ex.argtypes = [vp, vp, ctypes.c_int64, vp, ci, ci, ci, ctypes.c_float, vp, vp,
                                     vp, sz, ci, ci, vp]
         L.mla_decode_ex.restype = ci
-        L.mla_decode_typed.argtypes = [vp, vp, ctypes.c_int64, vp, ci, ci, ci, ci, ctypes.c_float, vp, vp,
+        L.mla_decode_typed.argtypes = [vp, vp, ctypes.c_int64, vp, ci, ci, ci, ci, ci, ctypes.c_float, vp, vp,
                                        vp, sz, ci, ci, vp]
         L.mla_decode_typed.restype = ci
         L.mla_status_string.argtypes = [ci]
@@ -75,8 +75,8 @@ def _check_tensors(q, kv_cache, cache_seqlens):
         raise TypeError("cache_seqlens must be int32")
     if not (q.is_cuda and kv_cache.is_cuda and cache_seqlens.is_cuda):
         raise ValueError("q, kv_cache and cache_seqlens must be device tensors")
-    if q.dim() != 4 or q.shape[1] != 1 or q.shape[3] != D_QK or not q.is_contiguous():
-        raise ValueError("q must be contiguous [batch, 1, heads, 576]")
+    if q.dim() != 4 or q.shape[1] < 1 or q.shape[3] != D_QK or not q.is_contiguous():
+        raise ValueError("q must be contiguous [batch, q_len, heads, 576]")
     if kv_cache.dim() != 3 or kv_cache.shape[0] != q.shape[0] or kv_cache.shape[2] != D_QK:
         raise ValueError("kv_cache must be [batch, max_seqlen_kv, 576]")
     if kv_cache.stride(2) != 1 or kv_cache.stride(1) != D_QK:
@@ -93,7 +93,8 @@ DTYPE_F16 = 1
 
 def mla_decode(q, kv_cache, cache_seqlens, scale, out=None, lse=None, workspace=None, num_workgroups=None,
                phases=None):
-    """out [batch, 1, heads, 512] fp32, lse [batch, heads] fp32 on the current stream (asynchronous).
+    """out [batch, q_len, heads, 512] fp32, lse [batch, heads] fp32 ([batch, q_len, heads] when
+    q_len > 1) on the current stream (asynchronous).
 
     q [batch, 1, 16, 576] and kv_cache [batch, max_seqlen_kv, 576] (batch stride free), both bf16
     or both fp16 (fp16 goes through ``mla_decode_typed``),
@@ -102,24 +103,26 @@ def mla_decode(q, kv_cache, cache_seqlens, scale, out=None, lse=None, workspace=
     split plan and ``phases`` selects the kernels (both go through ``mla_decode_ex``).
     """
     _check_tensors(q, kv_cache, cache_seqlens)
-    batch, _, heads, _ = q.shape
+    batch, q_len, heads, _ = q.shape
     max_seqlen = kv_cache.shape[1]
     dev = q.device
-    need, _ = mla_decode_workspace_size(batch, heads, max_seqlen, int(num_workgroups or 0))
+    need, _ = mla_decode_workspace_size(batch * q_len, heads, max_seqlen, int(num_workgroups or 0))
     if out is None:
-        out = torch.empty((batch, 1, heads, D_V), dtype=torch.float32, device=dev)
+        out = torch.empty((batch, q_len, heads, D_V), dtype=torch.float32, device=dev)
     if lse is None:
-        lse = torch.empty((batch, heads), dtype=torch.float32, device=dev)
+        lse = torch.empty((batch, heads) if q_len == 1 else (batch, q_len, heads), dtype=torch.float32, device=dev)
     if workspace is None:
         workspace = torch.empty((need,), dtype=torch.uint8, device=dev)
     stream = ctypes.c_void_p(torch.cuda.current_stream(dev).cuda_stream)
     head = [ctypes.c_void_p(q.data_ptr()), ctypes.c_void_p(kv_cache.data_ptr()), kv_cache.stride(0),
-            ctypes.c_void_p(cache_seqlens.data_ptr()), batch, heads, max_seqlen]
+            ctypes.c_void_p(cache_seqlens.data_ptr()), batch]
+    shape = [heads, max_seqlen]
     tail = [float(scale), ctypes.c_void_p(out.data_ptr()), ctypes.c_void_p(lse.data_ptr()),
             ctypes.c_void_p(workspace.data_ptr()), workspace.numel() * workspace.element_size()]
-    args = head + tail
-    if q.dtype == torch.float16:
-        st = lib().mla_decode_typed(*head, DTYPE_F16, *tail, int(num_workgroups or 0),
+    args = head + shape + tail
+    if q.dtype == torch.float16 or q_len != 1:
+        st = lib().mla_decode_typed(*head, q_len, *shape, DTYPE_F16 if q.dtype == torch.float16 else DTYPE_BF16,
+                                    *tail, int(num_workgroups or 0),
                                     int(PHASE_SPLIT | PHASE_COMBINE if phases is None else phases), stream)
         where = "mla_decode_typed"
     elif num_workgroups is None and phases is None:

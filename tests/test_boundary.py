@@ -34,11 +34,11 @@ def test_status_strings():
 
 
 @pytest.mark.parametrize("batch,num_wg", [(1, 256), (16, 256), (32, 304), (3, 1), (1024, 64)])
-def test_workspace_size_is_one_slot_per_workgroup_and_sequence(batch, num_wg):
+def test_workspace_size_is_one_slot_per_workgroup_and_sequence_plus_eight(batch, num_wg):
     nbytes, used = mla.mla_decode_workspace_size(batch, 16, 65536, num_workgroups=num_wg)
     assert used == num_wg
     slot = 16 * 512 * 4 + 16 * 4
-    assert (num_wg + batch) * slot <= nbytes <= (num_wg + batch) * slot + 16
+    assert (num_wg + batch + 8) * slot <= nbytes <= (num_wg + batch + 8) * slot + 16
     # independent of the KV length: the lengths live on the device
     assert mla.mla_decode_workspace_size(batch, 16, 7, num_workgroups=num_wg) == (nbytes, used)
 
@@ -88,6 +88,19 @@ def test_decode_argument_errors_come_before_any_device_work():
     assert _call(phases=8) == E.MLA_ERR_INVALID_ARG
     need, _ = mla.mla_decode_workspace_size(2, 16, 4096, 256)
     assert _call(ws_bytes=need - 1) == E.MLA_ERR_WORKSPACE_TOO_SMALL
+
+
+def test_typed_entry_argument_errors():
+    vp = ctypes.c_void_p
+
+    def call(dtype=0, q_len=1, batch=2):
+        return mla.lib().mla_decode_typed(vp(0x1000), vp(0x2000), 4096 * 576, vp(0x3000), batch, q_len, 16, 4096, dtype,
+                                          0.1, vp(0x4000), vp(0x5000), vp(0x6000), 1 << 30, 256, 3, None)
+    assert call(dtype=2) == mla.MLA_ERR_INVALID_ARG
+    assert call(dtype=-1) == mla.MLA_ERR_INVALID_ARG
+    assert call(q_len=0) == mla.MLA_ERR_UNSUPPORTED_SHAPE
+    assert call(q_len=9) == mla.MLA_ERR_UNSUPPORTED_SHAPE
+    assert call(batch=0) == mla.MLA_ERR_INVALID_ARG
 
 
 def test_binding_rejects_host_tensors():

@@ -234,3 +234,51 @@ def test_fp16_benchmark_configs_full_parity(oracle, cfg):
     print("case fp16 config", cfg, "oracle", flush=True)
     ref_o, ref_l = _oracle_f16(oracle, q, kv, l)
     _check_f16(out, lse, ref_o, ref_l, "fp16 config %d" % cfg)
+
+
+# ---- more than one query token per sequence (Section 3.1: one or two tokens per decoding step) ------
+
+def _oracle_general(oracle, q, kv, lens, dtype):
+    return oracle.decode_general(inputs.bits16(q), inputs.bits16(kv), lens.numpy(), inputs.SCALE, inputs.D_V,
+                                 dtype=oracle.F16 if dtype == torch.float16 else oracle.BF16)
+
+
+def _run_general(q, kv, lens, num_wg=None):
+    dev = _dev()
+    out, lse = mla.mla_decode(q.to(dev), kv.to(dev), lens.to(dev), inputs.SCALE, num_workgroups=num_wg)
+    torch.cuda.synchronize()
+    b, ql = q.shape[0], q.shape[1]
+    return (out.cpu().numpy().reshape(b * ql, 16, inputs.D_V).astype(np.float64),
+            lse.cpu().numpy().reshape(b * ql, 16).astype(np.float64))
+
+
+@pytest.mark.parametrize("q_len", [2, 3, 8])
+@pytest.mark.parametrize("num_wg", [None, 1, 5, 300])
+def test_several_query_tokens_small_ragged(oracle, q_len, num_wg):
+    # lengths below q_len leave the first query tokens without any row (out 0, lse -inf)
+    lens = [0, 1, 2, 3, 31, 33, 128, 129, 700, 1000, 257, 640]
+    q, kv, l = inputs.make_inputs(len(lens), 1000, lens, seed=401 + q_len, poison_tail=True, q_len=q_len)
+    ref_o, ref_l = _oracle_general(oracle, q, kv, l, torch.bfloat16)
+    print("case q_len", q_len, "num_wg", num_wg, flush=True)
+    out, lse = _run_general(q, kv, l, num_wg=num_wg)
+    _check(out, lse, ref_o.reshape(-1, 16, inputs.D_V), ref_l.reshape(-1, 16), label="q_len=%d num_wg=%s" % (q_len, num_wg))
+
+
+def test_two_query_tokens_fp16(oracle):
+    lens = [5, 640, 1, 2000]
+    q, kv, l = inputs.make_inputs(4, 2000, lens, seed=411, poison_tail=True, q_len=2, dtype=torch.float16)
+    ref_o, ref_l = _oracle_general(oracle, q, kv, l, torch.float16)
+    print("case q_len 2 fp16", flush=True)
+    out, lse = _run_general(q, kv, l)
+    _check_f16(out, lse, ref_o.reshape(-1, 16, inputs.D_V), ref_l.reshape(-1, 16), "q_len=2 fp16")
+
+
+def test_two_query_tokens_headline_shape(oracle):
+    """Batch 16, KV 65536, two query tokens: the launch configuration `bench.py --q-len 2` times."""
+    print("case q_len 2 headline generating", flush=True)
+    q, kv, l = inputs.make_inputs(16, 65536, None, seed=inputs.BASE_SEED + 42, q_len=2)
+    print("case q_len 2 headline gpu", flush=True)
+    out, lse = _run_general(q, kv, l)
+    print("case q_len 2 headline oracle", flush=True)
+    ref_o, ref_l = _oracle_general(oracle, q, kv, l, torch.bfloat16)
+    _check(out, lse, ref_o.reshape(-1, 16, inputs.D_V), ref_l.reshape(-1, 16), label="q_len=2 headline")
