@@ -72,6 +72,9 @@ def main():
     ap.add_argument("--config", type=int, default=4, help="benchmark configuration id (4 = headline)")
     ap.add_argument("--workgroups", type=int, default=0, help="force the number of workgroups (0 = automatic)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--orientation", choices=("transposed", "direct"), default="transposed",
+                    help="transposed = equations (1)-(4), the library's own choice; direct = Section 3.1 as written "
+                         "(comparison variant, bf16 and one query token only)")
     ap.add_argument("--q-len", type=int, default=1,
                     help="query tokens per sequence (1 = the headline metric; the paper names 1 or 2)")
     ap.add_argument("--dtype", choices=("bf16", "fp16"), default="bf16",
@@ -135,9 +138,11 @@ def main():
     alg_bytes += (args.q_len - 1) * batch * (16 * 576 * 2 + 16 * 512 * 4 + 16 * 4)
     alg_flops *= args.q_len
 
-    def step(i, phases=None):
+    orient = mla.ORIENT_DIRECT if args.orientation == "direct" else 0
+
+    def step(i, phases=mla.PHASE_SPLIT | mla.PHASE_COMBINE):
         mla.mla_decode(qd, kvs[i % n_buf], ld, inputs.SCALE, out=out, lse=lse, workspace=ws,
-                       num_workgroups=nwg, phases=phases)
+                       num_workgroups=nwg, phases=phases | orient)
 
     # ---- whole call ----------------------------------------------------------------------------
     for i in range(args.warmup):
@@ -213,7 +218,7 @@ def main():
                                    else "ragged uniform[%d,%d]" % cfg["ragged"]),
                    "total_kv_tokens": int(lens.sum()), "algorithmic_bytes_per_call": alg_bytes,
                    "algorithmic_flops_per_call": alg_flops, "workgroups": nwg_used,
-                   "kv_buffers_rotated": n_buf, "hbm_peak_frac_whole_call": tbps * 1e3 / HBM_PEAK_GBPS,
+                   "kv_buffers_rotated": n_buf, "orientation": args.orientation, "hbm_peak_frac_whole_call": tbps * 1e3 / HBM_PEAK_GBPS,
                    "tflops_whole_call": alg_flops / (ms_per_step * 1e-3) / 1e12},
         "roofline": {"bound": "hbm", "kernel": "mla_decode_split_kernel", "achieved": achieved_gbps,
                      "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": achieved_gbps / HBM_PEAK_GBPS, "traffic": traffic,

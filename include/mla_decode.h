@@ -108,11 +108,18 @@ mla_status_t mla_decode(const void *q, const void *kv_cache, int64_t kv_batch_st
  *                   merge of the workgroups' results; at least one of the two must be set and
  *                   mla_decode() is both.  Running the combine phase alone is only meaningful
  *                   after a split phase with the same arguments and workspace.
+ *                   MLA_ORIENT_DIRECT, added to the above, makes the split kernel compute in the
+ *                   original orientation of Section 3.1 (S = Q K^T and O = P V with heads on the
+ *                   matrix-core M axis) instead of the transposed one of equations (1)-(4): the
+ *                   same result up to fp32 summation order, kept so that the two orientations can
+ *                   be measured against each other.  bf16 and one query token only
+ *                   (else MLA_ERR_UNSUPPORTED_SHAPE).
  * All other arguments, and all error behaviour, are those of mla_decode().
  */
 #define MLA_UNIT_TOKENS 128
 #define MLA_PHASE_SPLIT 1
 #define MLA_PHASE_COMBINE 2
+#define MLA_ORIENT_DIRECT 8
 mla_status_t mla_decode_ex(const void *q, const void *kv_cache, int64_t kv_batch_stride,
                            const int32_t *cache_seqlens, int batch, int num_heads,
                            int max_seqlen_kv, float scale, float *out, float *lse,

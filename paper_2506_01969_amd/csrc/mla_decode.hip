@@ -199,7 +199,7 @@ constexpr float kLazyLog2 = 8.0f;   // the softmax reference moves only when exc
 // VGPR, multiply, and the result is copied back), so the accumulators' own live range has no
 // VALU use and the register allocator leaves them in place on the hot path.  This path is cold
 // (see kLazyLog2).
-__device__ __forceinline__ void rescale_accumulators(f32x4 (&o)[kDvTiles], float alpha, char *slot) {
+__device__ __forceinline__ void rescale_accumulators(f32x4 (&o)[kDvTiles], f32x4 alpha, char *slot) {
 #pragma unroll
     for (int c = 0; c < kDvTiles; c += 2) {
         *reinterpret_cast<volatile f32x4 *>(slot) = o[c];
@@ -214,7 +214,16 @@ __device__ __forceinline__ void rescale_accumulators(f32x4 (&o)[kDvTiles], float
 // Main kernel (steps a0-a7 of the hot path): persistent grid, workgroup k streams its share of
 // the unit stream segment by segment.
 // kTeam: several query tokens per sequence, i.e. several workgroups read every KV row.
-template <int kDtype, bool kTeam>
+//
+// kDirect = false is the transposed orientation of equations (1)-(4) described at the top of this
+// file.  kDirect = true is the original orientation of Section 3.1, kept for comparison:
+//     S = Q K^T   (heads on the MFMA M axis, tokens on N)
+//     O = P V     (heads on M, value columns on N, contraction over tokens)
+// The same registers feed the first product with the operands swapped, but its result now leaves a
+// lane with ONE token and four heads: the softmax maximum of a head needs a reduction across 16
+// lanes, every lane carries the running statistics of four heads, and P has to be transposed
+// across lanes (through 2 KB of LDS) before it can enter the second product.
+template <int kDtype, bool kTeam, bool kDirect>
 __global__ void __launch_bounds__(kThreads, 1) mla_decode_split_kernel(const Params p) {
     extern __shared__ __attribute__((aligned(16))) char smem[];
 
@@ -257,7 +266,12 @@ __global__ void __launch_bounds__(kThreads, 1) mla_decode_split_kernel(const Par
     const char *rd_k = my + r16 * kLdsRow + g * 16;       // K operand: token r16 (+16), chunk 4*kk + g
     // V^T operand through the transposing read: within each 16-lane group, lane j points at
     // row j/4, columns 4*(j%4)..+3 of a 4x16 block and receives column j, rows 0..3.
-    const char *rd_v = my + (4 * g + (r16 >> 2)) * kLdsRow + (r16 & 3) * 8;
+    // Tokens of the two reads, in the order of the other operand's 8 k-values: transposed
+    // orientation 4g..4g+3 and 16+4g..; direct orientation 8g..8g+3 and 8g+4..
+    const char *rd_v = my + ((kDirect ? 8 : 4) * g + (r16 >> 2)) * kLdsRow + (r16 & 3) * 8;
+    constexpr int kVSecond = (kDirect ? 4 : 16) * kLdsRow;
+    // direct orientation: P crosses lanes as fp32 [16 heads][32 tokens], in the rescale path's slot
+    float *p_tr = reinterpret_cast<float *>(smem + kRescaleOff + w * 2048);
     float *stat_m = reinterpret_cast<float *>(smem + kStatsOff);
     float *stat_l = stat_m + kWaves * kHeads;
     const unsigned lane16 = (unsigned)l * 16;               // global-load lane offsets (bytes)
@@ -317,6 +331,8 @@ __global__ void __launch_bounds__(kThreads, 1) mla_decode_split_kernel(const Par
         for (int ct = 0; ct < kDvTiles; ++ct) o[ct] = f32x4{0.f, 0.f, 0.f, 0.f};
         float m_run = -INFINITY;      // softmax reference of this lane's head (base-2 domain)
         float l_run = 0.f;            // this lane's share of the running sum
+        f32x4 m4 = {-INFINITY, -INFINITY, -INFINITY, -INFINITY};   // direct orientation: heads 4g .. 4g+3
+        f32x4 l4 = {0.f, 0.f, 0.f, 0.f};
 
         bool first_tile = true;
         while (cur < n_tiles) {
@@ -349,8 +365,13 @@ __global__ void __launch_bounds__(kThreads, 1) mla_decode_split_kernel(const Par
                         kb[kk % kKAhead][0] = *reinterpret_cast<const u32x4 *>(rd_k + (kk + kKAhead) * 64);
                         kb[kk % kKAhead][1] = *reinterpret_cast<const u32x4 *>(rd_k + 16 * kLdsRow + (kk + kKAhead) * 64);
                     }
-                    s0 = mfma_16x16x32<kDtype>(k0, qf[kk], s0);
-                    s1 = mfma_16x16x32<kDtype>(k1, qf[kk], s1);
+                    if constexpr (kDirect) {
+                        s0 = mfma_16x16x32<kDtype>(qf[kk], k0, s0);
+                        s1 = mfma_16x16x32<kDtype>(qf[kk], k1, s1);
+                    } else {
+                        s0 = mfma_16x16x32<kDtype>(k0, qf[kk], s0);
+                        s1 = mfma_16x16x32<kDtype>(k1, qf[kk], s1);
+                    }
                 }
                 // pin that interleaving for the instruction scheduler: reads first, then
                 // (2 MFMA, 2 LDS reads) per k-step, so LDS latency hides behind the MFMAs
@@ -361,6 +382,58 @@ __global__ void __launch_bounds__(kThreads, 1) mla_decode_split_kernel(const Par
                     if (kk + kKAhead < kKSteps) __builtin_amdgcn_sched_group_barrier(kSchedDsRead, 2, 0);
                 }
             }
+            float pr[8];
+            if constexpr (kDirect) {
+                // this lane holds, for token tb + r16 (s0) and tb + 16 + r16 (s1), heads 4g + i
+                const bool v0 = tb + r16 < t_end, v1 = tb + 16 + r16 < t_end;
+                f32x4 x0, x1, mx4;
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    x0[i] = v0 ? s0[i] * p.scale_log2e : -INFINITY;
+                    x1[i] = v1 ? s1[i] * p.scale_log2e : -INFINITY;
+                    float mm = fmaxf(x0[i], x1[i]);
+                    mm = wave_xor_max(mm, 1);
+                    mm = wave_xor_max(mm, 2);
+                    mm = wave_xor_max(mm, 4);
+                    mm = wave_xor_max(mm, 8);           // over the 16 lanes (tokens) of this k-group
+                    mx4[i] = mm;
+                }
+                if (first_tile) {
+                    m4 = mx4;
+                    first_tile = false;
+                } else {
+                    bool move = false;
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) move |= mx4[i] > m4[i] + kLazyLog2;
+                    if (__builtin_amdgcn_ballot_w64(move) != 0) {
+                        f32x4 alpha;
+#pragma unroll
+                        for (int i = 0; i < 4; ++i) {
+                            const float m_new = fmaxf(m4[i], mx4[i]);
+                            alpha[i] = __builtin_amdgcn_exp2f(m4[i] - m_new);
+                            m4[i] = m_new;
+                        }
+                        rescale_accumulators(o, alpha, smem + kRescaleOff + w * 2048 + l * 16);
+                        l4 *= alpha;
+                    }
+                }
+                // P[head 4g+i][token] -> LDS, then this lane takes head r16, tokens 8g .. 8g+7
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    const float p0 = __builtin_amdgcn_exp2f(x0[i] - m4[i]);
+                    const float p1 = __builtin_amdgcn_exp2f(x1[i] - m4[i]);
+                    l4[i] += p0 + p1;
+                    p_tr[(4 * g + i) * 32 + r16] = p0;
+                    p_tr[(4 * g + i) * 32 + 16 + r16] = p1;
+                }
+                const f32x4 lo4 = *reinterpret_cast<const f32x4 *>(p_tr + r16 * 32 + 8 * g);     // same wavefront:
+                const f32x4 hi4 = *reinterpret_cast<const f32x4 *>(p_tr + r16 * 32 + 8 * g + 4); // LDS keeps its order
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    pr[i] = lo4[i];
+                    pr[4 + i] = hi4[i];
+                }
+            } else {
             // this lane now holds, for head r16, tokens tb + 4g + i (s0[i]) and tb + 16 + 4g + i (s1[i])
 
             // ---- a4: scale (base-2 domain) and mask the tail ------------------------------
@@ -387,16 +460,16 @@ __global__ void __launch_bounds__(kThreads, 1) mla_decode_split_kernel(const Par
             } else if (__builtin_amdgcn_ballot_w64(mx > m_run + kLazyLog2) != 0) {
                 const float m_new = fmaxf(m_run, mx);
                 const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
-                rescale_accumulators(o, alpha, smem + kRescaleOff + w * 2048 + l * 16);
+                rescale_accumulators(o, f32x4{alpha, alpha, alpha, alpha}, smem + kRescaleOff + w * 2048 + l * 16);
                 l_run *= alpha;
                 m_run = m_new;
             }
-            float pr[8];
 #pragma unroll
             for (int i = 0; i < 8; ++i) {
                 pr[i] = __builtin_amdgcn_exp2f(x[i] - m_run);
                 l_run += pr[i];
             }
+            }   // orientation
 
             // P^T as B operand.  bf16: two-term split hi + lo (16 significant bits); fp16: one term
             // (11 significant bits; p <= 2^8 is far inside the fp16 range).
@@ -426,7 +499,7 @@ __global__ void __launch_bounds__(kThreads, 1) mla_decode_split_kernel(const Par
 #pragma unroll
                 for (int ct = 0; ct < kVAhead; ++ct) {
                     vb[ct][0] = read_tr16(rd_v + ct * 32);
-                    vb[ct][1] = read_tr16(rd_v + 16 * kLdsRow + ct * 32);
+                    vb[ct][1] = read_tr16(rd_v + kVSecond + ct * 32);
                 }
 #pragma unroll
                 for (int ct = 0; ct < kDvTiles; ++ct) {
@@ -435,10 +508,15 @@ __global__ void __launch_bounds__(kThreads, 1) mla_decode_split_kernel(const Par
                     __builtin_memcpy(&vt, vv, 16);
                     if (ct + kVAhead < kDvTiles) {
                         vb[ct % kVAhead][0] = read_tr16(rd_v + (ct + kVAhead) * 32);
-                        vb[ct % kVAhead][1] = read_tr16(rd_v + 16 * kLdsRow + (ct + kVAhead) * 32);
+                        vb[ct % kVAhead][1] = read_tr16(rd_v + kVSecond + (ct + kVAhead) * 32);
                     }
-                    o[ct] = mfma_16x16x32<kDtype>(vt, p_hi, o[ct]);
-                    if constexpr (kPTerms == 2) o[ct] = mfma_16x16x32<kDtype>(vt, p_lo, o[ct]);
+                    if constexpr (kDirect) {
+                        o[ct] = mfma_16x16x32<kDtype>(p_hi, vt, o[ct]);
+                        if constexpr (kPTerms == 2) o[ct] = mfma_16x16x32<kDtype>(p_lo, vt, o[ct]);
+                    } else {
+                        o[ct] = mfma_16x16x32<kDtype>(vt, p_hi, o[ct]);
+                        if constexpr (kPTerms == 2) o[ct] = mfma_16x16x32<kDtype>(vt, p_lo, o[ct]);
+                    }
                 }
                 __builtin_amdgcn_sched_group_barrier(kSchedDsRead, 2 * kVAhead, 1);
 #pragma unroll
@@ -453,36 +531,63 @@ __global__ void __launch_bounds__(kThreads, 1) mla_decode_split_kernel(const Par
         }
 
         // ---- a7: merge the four wavefronts, normalise, write (the epilogue of Algorithm 1) ----
-        l_run += __shfl_xor(l_run, 16, 64);
-        l_run += __shfl_xor(l_run, 32, 64);
-        if (g == 0) {
-            stat_m[w * kHeads + r16] = m_run;
-            stat_l[w * kHeads + r16] = l_run;
+        if constexpr (kDirect) {
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                float s = l4[i];
+                s += __shfl_xor(s, 1, 64);
+                s += __shfl_xor(s, 2, 64);
+                s += __shfl_xor(s, 4, 64);
+                s += __shfl_xor(s, 8, 64);
+                if (r16 == 0) {
+                    stat_m[w * kHeads + 4 * g + i] = m4[i];
+                    stat_l[w * kHeads + 4 * g + i] = s;
+                }
+            }
+        } else {
+            l_run += __shfl_xor(l_run, 16, 64);
+            l_run += __shfl_xor(l_run, 32, 64);
+            if (g == 0) {
+                stat_m[w * kHeads + r16] = m_run;
+                stat_l[w * kHeads + r16] = l_run;
+            }
         }
         // own accumulators into the own (now idle) tile: [ct][lane] x 16 B
 #pragma unroll
         for (int ct = 0; ct < kDvTiles; ++ct) *reinterpret_cast<f32x4 *>(my + ct * 1024 + l * 16) = o[ct];
         __syncthreads();
 
-        float m_tot = stat_m[r16];
-#pragma unroll
-        for (int ww = 1; ww < kWaves; ++ww) m_tot = fmaxf(m_tot, stat_m[ww * kHeads + r16]);
-        const bool none = (m_tot == -INFINITY);      // the whole workgroup drew no tile of this sequence
-        float f[kWaves];
-        float l_tot = 0.f;
-#pragma unroll
-        for (int ww = 0; ww < kWaves; ++ww) {
-            f[ww] = none ? 0.f : __builtin_amdgcn_exp2f(stat_m[ww * kHeads + r16] - m_tot);   // 0 for an idle wavefront
-            l_tot += f[ww] * stat_l[ww * kHeads + r16];
-        }
-        const float inv_l = none ? 0.f : 1.0f / l_tot;
-#pragma unroll
-        for (int ww = 0; ww < kWaves; ++ww) f[ww] *= inv_l;
-
+        // Statistics of the head(s) whose accumulator elements this lane holds: head r16 in all four
+        // elements (transposed orientation), or heads 4g .. 4g+3, one per element (direct orientation).
         const long long slot = ((long long)k + b) * p.q_len + j;
-        float *dst = direct ? p.out + (row * kHeads + r16) * kDv
-                            : p.part_out + (slot * kHeads + r16) * kDv;
-        // wavefront w finishes value tiles 8w .. 8w+7; lane holds head r16, columns 16ct + 4g .. +3
+        f32x4 f[kWaves];
+        float lse2_of[4];
+        constexpr int kStatHeads = kDirect ? 4 : 1;
+#pragma unroll
+        for (int i = 0; i < kStatHeads; ++i) {
+            const int hd = kDirect ? 4 * g + i : r16;
+            float m_tot = stat_m[hd];
+#pragma unroll
+            for (int ww = 1; ww < kWaves; ++ww) m_tot = fmaxf(m_tot, stat_m[ww * kHeads + hd]);
+            const bool none = (m_tot == -INFINITY);      // the whole workgroup drew no tile of this sequence
+            float fw[kWaves];
+            float l_tot = 0.f;
+#pragma unroll
+            for (int ww = 0; ww < kWaves; ++ww) {
+                fw[ww] = none ? 0.f : __builtin_amdgcn_exp2f(stat_m[ww * kHeads + hd] - m_tot);   // 0 for an idle wavefront
+                l_tot += fw[ww] * stat_l[ww * kHeads + hd];
+            }
+            const float inv_l = none ? 0.f : 1.0f / l_tot;
+#pragma unroll
+            for (int ww = 0; ww < kWaves; ++ww) {
+                if constexpr (kDirect) f[ww][i] = fw[ww] * inv_l;
+                else f[ww] = f32x4{fw[ww] * inv_l, fw[ww] * inv_l, fw[ww] * inv_l, fw[ww] * inv_l};
+            }
+            lse2_of[i] = none ? -INFINITY : m_tot + __builtin_amdgcn_logf(l_tot);   // v_log_f32 is log2
+        }
+
+        float *dst = direct ? p.out + row * kHeads * kDv : p.part_out + slot * kHeads * kDv;
+        // wavefront w finishes value tiles 8w .. 8w+7
 #pragma unroll
         for (int c = 0; c < kDvTiles / kWaves; ++c) {
             const int ct = w * (kDvTiles / kWaves) + c;
@@ -492,12 +597,20 @@ __global__ void __launch_bounds__(kThreads, 1) mla_decode_split_kernel(const Par
                 const f32x4 part = *reinterpret_cast<const f32x4 *>(smem + ww * kWaveLds + ct * 1024 + l * 16);
                 acc += part * f[ww];
             }
-            *reinterpret_cast<f32x4 *>(dst + ct * 16 + g * 4) = acc;   // equation (4): transpose by addressing
+            if constexpr (kDirect) {      // element i: head 4g + i, column 16 ct + r16
+#pragma unroll
+                for (int i = 0; i < 4; ++i) dst[(4 * g + i) * kDv + ct * 16 + r16] = acc[i];
+            } else {                      // head r16, columns 16 ct + 4g .. +3; equation (4): transpose by addressing
+                *reinterpret_cast<f32x4 *>(dst + r16 * kDv + ct * 16 + g * 4) = acc;
+            }
         }
-        if (w == 0 && g == 0) {
-            const float lse2 = none ? -INFINITY : m_tot + __builtin_amdgcn_logf(l_tot);   // v_log_f32 is log2
-            if (direct) p.lse[row * kHeads + r16] = lse2 * 0.6931471805599453f;
-            else p.part_lse[slot * kHeads + r16] = lse2;
+        if (w == 0 && (kDirect ? r16 == 0 : g == 0)) {
+#pragma unroll
+            for (int i = 0; i < kStatHeads; ++i) {
+                const int hd = kDirect ? 4 * g + i : r16;
+                if (direct) p.lse[row * kHeads + hd] = lse2_of[i] * 0.6931471805599453f;
+                else p.part_lse[slot * kHeads + hd] = lse2_of[i];
+            }
         }
 
         // next sequence this workgroup is bound to: the following one with at least one unit
@@ -624,14 +737,17 @@ mla_status_t launch(const void *q, const void *kv_cache, int64_t kv_batch_stride
 
     // the main kernel needs more dynamic LDS than the default limit: raise it once per device
     static std::mutex mu;
-    static bool attr_done[64][4] = {};
+    static bool attr_done[64][5] = {};
     int dev = 0;
     if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return MLA_ERR_HIP;
     typedef void (*kernel_fn)(const Params);
-    static const kernel_fn kernels[4] = {
-        mla_decode_split_kernel<MLA_DTYPE_BF16, false>, mla_decode_split_kernel<MLA_DTYPE_F16, false>,
-        mla_decode_split_kernel<MLA_DTYPE_BF16, true>, mla_decode_split_kernel<MLA_DTYPE_F16, true>};
-    const int variant = (q_len > 1 ? 2 : 0) + (dtype == MLA_DTYPE_F16 ? 1 : 0);
+    static const kernel_fn kernels[5] = {
+        mla_decode_split_kernel<MLA_DTYPE_BF16, false, false>, mla_decode_split_kernel<MLA_DTYPE_F16, false, false>,
+        mla_decode_split_kernel<MLA_DTYPE_BF16, true, false>, mla_decode_split_kernel<MLA_DTYPE_F16, true, false>,
+        mla_decode_split_kernel<MLA_DTYPE_BF16, false, true>};
+    const bool direct_orientation = (flags & MLA_ORIENT_DIRECT) != 0;
+    if (direct_orientation && (q_len > 1 || dtype != MLA_DTYPE_BF16)) return MLA_ERR_UNSUPPORTED_SHAPE;
+    const int variant = direct_orientation ? 4 : (q_len > 1 ? 2 : 0) + (dtype == MLA_DTYPE_F16 ? 1 : 0);
     const kernel_fn split_fn = kernels[variant];
     {
         std::lock_guard<std::mutex> lock(mu);
@@ -722,7 +838,7 @@ mla_status_t mla_decode_typed(const void *q, const void *kv_cache, int64_t kv_ba
                                max_seqlen_kv, scale, out, lse, workspace);
     if (st != MLA_OK) return st;
     if (num_workgroups < 0 || num_workgroups > kMaxWorkgroups) return MLA_ERR_INVALID_ARG;
-    if ((flags & ~(MLA_PHASE_SPLIT | MLA_PHASE_COMBINE)) != 0) return MLA_ERR_INVALID_ARG;
+    if ((flags & ~(MLA_PHASE_SPLIT | MLA_PHASE_COMBINE | MLA_ORIENT_DIRECT)) != 0) return MLA_ERR_INVALID_ARG;
     if ((flags & (MLA_PHASE_SPLIT | MLA_PHASE_COMBINE)) == 0) return MLA_ERR_INVALID_ARG;
     if (num_workgroups == 0) {
         st = planned_workgroups(q_len, &num_workgroups, nullptr);

@@ -87,6 +87,7 @@ def _check_tensors(q, kv_cache, cache_seqlens):
 
 PHASE_SPLIT = 1
 PHASE_COMBINE = 2
+ORIENT_DIRECT = 8
 DTYPE_BF16 = 0
 DTYPE_F16 = 1
 

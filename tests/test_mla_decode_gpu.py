@@ -282,3 +282,50 @@ def test_two_query_tokens_headline_shape(oracle):
     print("case q_len 2 headline oracle", flush=True)
     ref_o, ref_l = _oracle_general(oracle, q, kv, l, torch.bfloat16)
     _check(out, lse, ref_o.reshape(-1, 16, inputs.D_V), ref_l.reshape(-1, 16), label="q_len=2 headline")
+
+
+# ---- the original (non-transposed) orientation of Section 3.1, kept for the comparison of the two ----
+
+DIRECT = mla.PHASE_SPLIT | mla.PHASE_COMBINE | mla.ORIENT_DIRECT
+
+
+def _run_direct(q, kv, lens, num_wg=None):
+    dev = _dev()
+    out, lse = mla.mla_decode(q.to(dev), kv.to(dev), lens.to(dev), inputs.SCALE, num_workgroups=num_wg, phases=DIRECT)
+    torch.cuda.synchronize()
+    return (out.cpu().numpy().reshape(q.shape[0], 16, inputs.D_V).astype(np.float64),
+            lse.cpu().numpy().astype(np.float64))
+
+
+@pytest.mark.parametrize("num_wg", [None, 1, 7, 300])
+def test_direct_orientation_small_ragged(oracle, num_wg):
+    lens = [1, 31, 32, 33, 127, 128, 129, 700, 1000, 0, 513, 640]
+    q, kv, l = inputs.make_inputs(len(lens), 1000, lens, seed=501, poison_tail=True)
+    ref_o, ref_l = _oracle(oracle, q, kv, l)
+    print("case direct small_ragged num_wg", num_wg, flush=True)
+    out, lse = _run_direct(q, kv, l, num_wg=num_wg)
+    _check(out, lse, ref_o, ref_l, label="direct small_ragged num_wg=%s" % num_wg)
+
+
+def test_direct_orientation_rescale_path(oracle):
+    # per-head rescale factors: heads whose maxima jump at different tiles
+    n = 2048
+    q, kv, l = inputs.make_inputs(2, n, [n, n - 77], seed=502)
+    ramp = torch.linspace(0.05, 6.0, n).view(1, n, 1)
+    kv = (kv.float() * ramp).to(torch.bfloat16)
+    ref_o, ref_l = _oracle(oracle, q, kv, l)
+    print("case direct growing_scores", flush=True)
+    out, lse = _run_direct(q, kv, l, num_wg=2)
+    assert np.abs(out - ref_o).max() / np.abs(ref_o).max() < 2e-5
+    assert np.abs(lse - ref_l).max() < 5e-5
+
+
+@pytest.mark.parametrize("cfg", [1, 4, 5])
+def test_direct_orientation_benchmark_configs(oracle, cfg):
+    print("case direct config", cfg, "generating", flush=True)
+    q, kv, l = inputs.make_config(cfg, poison_tail=True)
+    print("case direct config", cfg, "gpu", flush=True)
+    out, lse = _run_direct(q, kv, l)
+    print("case direct config", cfg, "oracle", flush=True)
+    ref_o, ref_l = _oracle(oracle, q, kv, l)
+    _check(out, lse, ref_o, ref_l, label="direct config %d" % cfg)
