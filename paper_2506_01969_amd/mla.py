@@ -97,11 +97,12 @@ def mla_decode(q, kv_cache, cache_seqlens, scale, out=None, lse=None, workspace=
     """out [batch, q_len, heads, 512] fp32, lse [batch, heads] fp32 ([batch, q_len, heads] when
     q_len > 1) on the current stream (asynchronous).
 
-    q [batch, 1, 16, 576] and kv_cache [batch, max_seqlen_kv, 576] (batch stride free), both bf16
-    or both fp16 (fp16 goes through ``mla_decode_typed``),
-    cache_seqlens [batch] int32, all on the current device.  ``out``, ``lse`` and ``workspace``
-    (a uint8 tensor) are allocated with torch when not given.  ``num_workgroups`` forces the
-    split plan and ``phases`` selects the kernels (both go through ``mla_decode_ex``).
+    q [batch, q_len, 16, 576] and kv_cache [batch, max_seqlen_kv, 576] (batch stride free), both
+    bf16 or both fp16; cache_seqlens [batch] int32 (counting the q_len new tokens, which attend
+    causally among themselves); all on the current device.  ``out``, ``lse`` and ``workspace`` (a
+    uint8 tensor) are allocated with torch when not given.  ``num_workgroups`` forces the split
+    plan; ``phases`` is the ``flags`` argument of ``mla_decode_ex`` (PHASE_SPLIT, PHASE_COMBINE,
+    ORIENT_DIRECT).  fp16 or q_len > 1 go through ``mla_decode_typed``.
     """
     _check_tensors(q, kv_cache, cache_seqlens)
     batch, q_len, heads, _ = q.shape

@@ -65,6 +65,19 @@ def test_small_ragged_elementwise(oracle, num_wg):
     _check(out, lse, ref_o, ref_l, label="small_ragged num_wg=%s" % num_wg)
 
 
+@pytest.mark.parametrize("num_wg", [None, 7, 300])
+def test_many_short_sequences(oracle, num_wg):
+    """More sequences than one wavefront scans at once (64), many per workgroup, empty ones between."""
+    g = torch.Generator().manual_seed(1234)
+    lens = torch.randint(0, 401, (300,), generator=g).tolist()
+    lens[5] = lens[6] = lens[64] = lens[128] = lens[299] = 0
+    q, kv, l = inputs.make_inputs(300, 400, lens, seed=110, poison_tail=True)
+    ref_o, ref_l = _oracle(oracle, q, kv, l)
+    print("case many_short num_wg", num_wg, flush=True)
+    out, lse = _run(q, kv, l, num_wg=num_wg)
+    _check(out, lse, ref_o, ref_l, label="many_short num_wg=%s" % num_wg)
+
+
 def test_empty_and_full_sequences(oracle):
     lens = [0, 384, 0, 1]
     q, kv, l = inputs.make_inputs(4, 384, lens, seed=102, poison_tail=True)
@@ -262,6 +275,17 @@ def test_several_query_tokens_small_ragged(oracle, q_len, num_wg):
     print("case q_len", q_len, "num_wg", num_wg, flush=True)
     out, lse = _run_general(q, kv, l, num_wg=num_wg)
     _check(out, lse, ref_o.reshape(-1, 16, inputs.D_V), ref_l.reshape(-1, 16), label="q_len=%d num_wg=%s" % (q_len, num_wg))
+
+
+def test_two_query_tokens_many_sequences(oracle):
+    g = torch.Generator().manual_seed(4321)
+    lens = torch.randint(0, 300, (70,), generator=g).tolist()
+    q, kv, l = inputs.make_inputs(70, 300, lens, seed=412, poison_tail=True, q_len=2)
+    ref_o, ref_l = _oracle_general(oracle, q, kv, l, torch.bfloat16)
+    for nwg in (None, 9):
+        print("case q_len 2 many sequences num_wg", nwg, flush=True)
+        out, lse = _run_general(q, kv, l, num_wg=nwg)
+        _check(out, lse, ref_o.reshape(-1, 16, inputs.D_V), ref_l.reshape(-1, 16), label="q_len=2 many num_wg=%s" % nwg)
 
 
 def test_two_query_tokens_fp16(oracle):
