@@ -169,14 +169,6 @@ def main():
     durs = sorted(a.elapsed_time(b) for a, b in ev)
     split_ms_avg = sum(durs) / len(durs)
     split_ms_med = durs[len(durs) // 2]
-    # combine alone, for the record
-    evc = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
-    for i in range(args.steps):
-        evc[i][0].record()
-        step(i, mla.PHASE_COMBINE)
-        evc[i][1].record()
-    torch.cuda.synchronize()
-    comb_ms_avg = sum(a.elapsed_time(b) for a, b in evc) / len(evc)
     achieved_gbps = alg_bytes / (split_ms_avg * 1e-3) / 1e9
 
     traffic = None
@@ -222,8 +214,7 @@ def main():
                    "tflops_whole_call": alg_flops / (ms_per_step * 1e-3) / 1e12},
         "roofline": {"bound": "hbm", "kernel": "mla_decode_split_kernel", "achieved": achieved_gbps,
                      "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": achieved_gbps / HBM_PEAK_GBPS, "traffic": traffic,
-                     "avg_us": split_ms_avg * 1e3, "median_us": split_ms_med * 1e3,
-                     "combine_kernel_avg_us": comb_ms_avg * 1e3},
+                     "avg_us": split_ms_avg * 1e3, "median_us": split_ms_med * 1e3},
         "cpu_baseline": cpu,
     }
     print(json.dumps(line))
