@@ -26,7 +26,8 @@
 // Each wavefront is an independent online-softmax worker (the m / l / rescale recurrence of
 // Algorithm 1) over every 4th 32-token tile of the segment, with a
 // private LDS tile, so the main loop has no barrier.  A tile is fetched with 16-byte coalesced
-// global loads into registers (in flight while the previous tile is being computed), written
+// global loads into registers (in flight while the previous tile is being computed; each register
+// is refilled with its piece of the next tile the moment it has been copied to LDS), written
 // once to LDS, and read twice from LDS: as the K operand (ds_read_b128) and, through the
 // transposing LDS read ds_read_b64_tr_b16, as the V^T operand.  The four wavefronts of a
 // workgroup merge their (m, l, O) through LDS at the end of the segment; a sequence
@@ -340,12 +341,30 @@ __global__ void __launch_bounds__(kThreads, 1) mla_decode_split_kernel(const Par
 
             // ---- a2: registers -> private LDS tile ----------------------------------------
             // chunk c = 64 i + l goes to row c / 72, column chunk c % 72: byte 16 (c + c / 72)
+            // Each piece's register is refilled with the same piece of the next tile as soon as it
+            // has been written to LDS, so this wavefront keeps 35 requests in flight at all times
+            // instead of draining to none before it asks again.
+            if (nxt < n_tiles) {
+                const int ntb = t_begin + nxt * kTile;
+                const int valid_rows = min(n - ntb, kTile);                 // >= 1
+                const int last_chunk16 = (valid_rows * (kRowBytes / 16) - 1) * 16;
+                const char *tile_base = kv_b + (long long)ntb * kRowBytes;
 #pragma unroll
-            for (int i = 0; i < kTileLoads; ++i)
-                *reinterpret_cast<u32x4 *>(wr_flat[i % 9] + i * 1024 + ((i * 64) / 72) * 16) = st[i];
-
-            // the next tile of this wavefront goes in flight now and lands while this one is computed
-            if (nxt < n_tiles) issue_loads(nxt);
+                for (int i = 0; i < kTileLoads; ++i) {
+                    *reinterpret_cast<u32x4 *>(wr_flat[i % 9] + i * 1024 + ((i * 64) / 72) * 16) = st[i];
+                    const int piece = min(i * 1024, last_chunk16);          // scalar
+                    st[i] = load_stream16<kTeam>(tile_base + piece, min(lane16, (unsigned)(last_chunk16 - piece)));
+                }
+#pragma unroll
+                for (int i = 0; i < kTileLoads; ++i) {
+                    __builtin_amdgcn_sched_group_barrier(0x200, 1, 2);      // one LDS write
+                    __builtin_amdgcn_sched_group_barrier(0x020, 1, 2);      // one global load
+                }
+            } else {
+#pragma unroll
+                for (int i = 0; i < kTileLoads; ++i)
+                    *reinterpret_cast<u32x4 *>(wr_flat[i % 9] + i * 1024 + ((i * 64) / 72) * 16) = st[i];
+            }
 
             // ---- a3: S^T = K Q^T for tokens 0..15 and 16..31 of the tile (equation (1)) --
             // LDS reads run kKAhead k-steps ahead of the MFMAs that consume them.
