@@ -671,34 +671,44 @@ __global__ void __launch_bounds__(kCombineThreads) mla_decode_combine_kernel(con
     const int lstep = p.q_len * kHeads;
     const long long ostep = (long long)p.q_len * kHeads * kDv;
     const float *pl = p.part_lse + first_slot * kHeads + h;
-    float m = -INFINITY;
-    for (int s = 0; s < ns; ++s) m = fmaxf(m, pl[s * lstep]);
+    const float *po = p.part_out + (first_slot * kHeads + h) * kDv + t * 4;
+    // The kernel is a chain of memory round trips, so every load of up to kBatch pieces (their
+    // log-sum-exps and this thread's four columns) is issued before anything is waited for; more
+    // pieces than that are folded in batch by batch with the same running-maximum recurrence.
+    constexpr int kBatch = 16;
+    float m = -INFINITY, sum = 0.f;
+    f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+    for (int s0 = 0; s0 < ns; s0 += kBatch) {
+        float ls[kBatch];
+        f32x4 v[kBatch];
+#pragma unroll
+        for (int i = 0; i < kBatch; ++i) {
+            const bool on = s0 + i < ns;
+            ls[i] = on ? pl[(s0 + i) * lstep] : -INFINITY;
+            v[i] = on ? *reinterpret_cast<const f32x4 *>(po + (s0 + i) * ostep) : f32x4{0.f, 0.f, 0.f, 0.f};
+        }
+        float mb = m;
+#pragma unroll
+        for (int i = 0; i < kBatch; ++i) mb = fmaxf(mb, ls[i]);
+        if (mb == -INFINITY) continue;        // nothing but empty pieces so far
+        const float keep = __builtin_amdgcn_exp2f(m - mb);     // 0 when m is still -inf
+        sum *= keep;
+        acc *= keep;
+#pragma unroll
+        for (int i = 0; i < kBatch; ++i) {
+            const float wgt = __builtin_amdgcn_exp2f(ls[i] - mb);   // 0 for an empty or absent piece
+            sum += wgt;
+            if (ls[i] != -INFINITY) acc += v[i] * wgt;              // (an empty piece holds zeros anyway)
+        }
+        m = mb;
+    }
     if (m == -INFINITY) {                     // a query token that sees no row at all (length < q_len)
         *reinterpret_cast<f32x4 *>(out) = f32x4{0.f, 0.f, 0.f, 0.f};
         if (t == 0) p.lse[row * kHeads + h] = -INFINITY;
         return;
     }
-    float sum = 0.f;
-    for (int s = 0; s < ns; ++s) sum += __builtin_amdgcn_exp2f(pl[s * lstep] - m);
     const float tot = m + __builtin_amdgcn_logf(sum);
-    const float *po = p.part_out + (first_slot * kHeads + h) * kDv + t * 4;
-    f32x4 acc = {0.f, 0.f, 0.f, 0.f};
-    int s = 0;
-    for (; s + 8 <= ns; s += 8) {             // eight independent loads in flight per thread
-        f32x4 v[8];
-        float wgt[8];
-#pragma unroll
-        for (int j = 0; j < 8; ++j) {
-            v[j] = *reinterpret_cast<const f32x4 *>(po + (s + j) * ostep);
-            wgt[j] = __builtin_amdgcn_exp2f(pl[(s + j) * lstep] - tot);
-        }
-#pragma unroll
-        for (int j = 0; j < 8; ++j) acc += v[j] * wgt[j];
-    }
-    for (; s < ns; ++s) {
-        const float wgt = __builtin_amdgcn_exp2f(pl[s * lstep] - tot);
-        acc += *reinterpret_cast<const f32x4 *>(po + s * ostep) * wgt;
-    }
+    acc *= 1.0f / sum;
     *reinterpret_cast<f32x4 *>(out) = acc;
     if (t == 0) p.lse[row * kHeads + h] = tot * 0.6931471805599453f;
 }
