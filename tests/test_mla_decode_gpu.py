@@ -180,6 +180,39 @@ def test_phases_split_then_combine_equals_one_call():
     assert torch.equal(o1, o2) and torch.equal(s1, s2)
 
 
+def test_call_can_be_captured_in_a_graph_and_replayed(oracle):
+    """The library allocates nothing and never synchronises, so a call can be recorded into a HIP
+    graph.  Every replay, with eager work and synchronisation in between, must reproduce the eager
+    result bit for bit (the tile assignment is static)."""
+    dev = _dev()
+    q, kv, l = inputs.make_inputs(4, 3000, [3000, 1, 1500, 640], seed=120, poison_tail=True)
+    ref_o, ref_l = _oracle(oracle, q, kv, l)
+    qd, kvd, ld = q.to(dev), kv.to(dev), l.to(dev)
+    need, _ = mla.mla_decode_workspace_size(4, 16, 3000, 0)
+    ws = torch.empty((need,), dtype=torch.uint8, device=dev)
+    out = torch.empty((4, 1, 16, 512), dtype=torch.float32, device=dev)
+    lse = torch.empty((4, 16), dtype=torch.float32, device=dev)
+    print("case graph", flush=True)
+    mla.mla_decode(qd, kvd, ld, inputs.SCALE, out=out, lse=lse, workspace=ws)      # eager; also the one-time set-up
+    torch.cuda.synchronize()
+    eager_o, eager_l = out.clone(), lse.clone()
+    graph = torch.cuda.CUDAGraph()
+    side = torch.cuda.Stream(device=dev)
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            mla.mla_decode(qd, kvd, ld, inputs.SCALE, out=out, lse=lse, workspace=ws)
+    torch.cuda.synchronize()
+    for rep_ in range(4):
+        out.fill_(float("nan")); lse.fill_(float("nan")); ws.fill_(0xFF)     # eager work between replays
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(out, eager_o) and torch.equal(lse, eager_l), "replay %d" % rep_
+    _check(out.cpu().numpy().reshape(4, 16, 512).astype(np.float64), lse.cpu().numpy().astype(np.float64),
+           ref_o, ref_l, label="graph replay")
+
+
 def test_runtime_errors_leave_outputs_untouched():
     dev = _dev()
     q, kv, l = inputs.make_inputs(2, 512, None, seed=109)
