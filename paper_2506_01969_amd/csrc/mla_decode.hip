@@ -277,49 +277,56 @@ __global__ void __launch_bounds__(kThreads, 1) mla_decode_split_kernel(const Par
     float *stat_l = stat_m + kWaves * kHeads;
     const unsigned lane16 = (unsigned)l * 16;               // global-load lane offsets (bytes)
 
-    int cur_unit = u_lo;
-    while (cur_unit < u_hi) {
-        const int n = clamped_len(p, b);
-        const int ub = units_of(n);                            // > 0
-        const int u_begin = cur_unit - seq_first;
+    // ---- the piece being worked on (this team's units of one sequence) -----------------------
+    int n, ub, t_begin, t_end, n_tiles;
+    bool direct;
+    const char *kv_b;
+    long long row;                    // row of q, out and lse
+    auto set_piece = [&](int first_unit) {          // uses b and seq_first
+        n = clamped_len(p, b);
+        ub = units_of(n);                                      // > 0
+        const int u_begin = first_unit - seq_first;
         const int u_end = min(u_hi - seq_first, ub);           // > u_begin
-        const int t_begin = u_begin * kUnit;
-        const int t_end = min(visible_len(p, n, j), u_end * kUnit);      // may be <= t_begin: nothing visible here
-        const int n_tiles = t_end > t_begin ? (t_end - t_begin + kTile - 1) / kTile : 0;
-        const bool direct = (u_begin == 0 && u_end == ub);     // this team covers the whole sequence
-        const char *kv_b = p.kv + (long long)b * p.kv_batch_bytes;
-        const long long row = (long long)b * p.q_len + j;     // row of q, out and lse
+        t_begin = u_begin * kUnit;
+        t_end = min(visible_len(p, n, j), u_end * kUnit);      // may be <= t_begin: nothing visible here
+        n_tiles = t_end > t_begin ? (t_end - t_begin + kTile - 1) / kTile : 0;
+        direct = (u_begin == 0 && u_end == ub);                // this team covers the whole sequence
+        kv_b = p.kv + (long long)b * p.kv_batch_bytes;
+        row = (long long)b * p.q_len + j;
+    };
 
-        u32x4 st[kTileLoads];         // one tile in flight: 36 x 16 B per lane
-
-        // A tile is 32 consecutive rows = 36,864 contiguous bytes, fetched as 36 pieces of 1 KB
-        // (lane l of piece i reads 16-byte chunk 64 i + l).  Fully sequential 1 KB requests
-        // stream measurably faster from HBM than row-shaped ones.  Rows past the end of the
-        // sequence are never fetched: chunk indices are clamped to the last valid chunk (the
-        // scores of those rows are masked below, so whatever lands there has weight zero and
-        // is finite data of a valid row).
-        auto issue_loads = [&](int tile) {
-            const int tb = t_begin + tile * kTile;
-            const int valid_rows = min(n - tb, kTile);                 // >= 1
-            const int last_chunk16 = (valid_rows * (kRowBytes / 16) - 1) * 16;   // byte offset of the last valid chunk
-            const char *tile_base = kv_b + (long long)tb * kRowBytes;
+    u32x4 st[kTileLoads];             // one tile in flight: 36 x 16 B per lane
+    // A tile is 32 consecutive rows = 36,864 contiguous bytes, fetched as 36 pieces of 1 KB
+    // (lane l of piece i reads 16-byte chunk 64 i + l).  Fully sequential 1 KB requests
+    // stream measurably faster from HBM than row-shaped ones.  Rows past the end of the
+    // sequence are never fetched: chunk indices are clamped to the last valid chunk (the
+    // scores of those rows are masked below, so whatever lands there has weight zero and
+    // is finite data of a valid row).
+    auto issue_loads = [&](int tile) {              // tile of the current piece
+        const int tb = t_begin + tile * kTile;
+        const int valid_rows = min(n - tb, kTile);                 // >= 1
+        const int last_chunk16 = (valid_rows * (kRowBytes / 16) - 1) * 16;   // byte offset of the last valid chunk
+        const char *tile_base = kv_b + (long long)tb * kRowBytes;
 #pragma unroll
-            for (int i = 0; i < kTileLoads; ++i) {
-                const int piece = min(i * 1024, last_chunk16);          // scalar
-                st[i] = load_stream16<kTeam>(tile_base + piece, min(lane16, (unsigned)(last_chunk16 - piece)));
-            }
-        };
-        // ---- a1: Q^T as the MFMA B operand: lane (head r16, k-group g) holds dims 32*kk + 8*g .. +8
-        u32x4 qf[kKSteps];
-        {
-            const u32x4 *qp = reinterpret_cast<const u32x4 *>(p.q + (row * kHeads + r16) * kRowBytes) + g;
-#pragma unroll
-            for (int kk = 0; kk < kKSteps; ++kk) qf[kk] = qp[4 * kk];
+        for (int i = 0; i < kTileLoads; ++i) {
+            const int piece = min(i * 1024, last_chunk16);          // scalar
+            st[i] = load_stream16<kTeam>(tile_base + piece, min(lane16, (unsigned)(last_chunk16 - piece)));
         }
+    };
+    // ---- a1: Q^T as the MFMA B operand: lane (head r16, k-group g) holds dims 32*kk + 8*g .. +8
+    u32x4 qf[kKSteps];
+    auto load_q = [&]() {                           // q of the current piece's row
+        const u32x4 *qp = reinterpret_cast<const u32x4 *>(p.q + (row * kHeads + r16) * kRowBytes) + g;
+#pragma unroll
+        for (int kk = 0; kk < kKSteps; ++kk) qf[kk] = qp[4 * kk];
+    };
 
-        // this wavefront's tiles of the segment: w, w + 4, w + 8, ...
+    set_piece(u_lo);
+    load_q();
+    if (w < n_tiles) issue_loads(w);
+    while (true) {
+        // this wavefront's tiles of the piece: w, w + 4, w + 8, ...; q and the first tile are on their way
         int cur = w, nxt = w + kWaves;
-        if (cur < n_tiles) issue_loads(cur);
 
         // Q must be resident before the tile loop.  It was requested ahead of the first tile, so
         // this waits for Q alone; left to the loop, the wait for Q would be re-evaluated on every
@@ -549,6 +556,22 @@ __global__ void __launch_bounds__(kThreads, 1) mla_decode_split_kernel(const Par
             nxt += kWaves;
         }
 
+        // ---- the next piece's q and first tile go in flight before this piece's epilogue, so a
+        // workgroup whose share crosses a sequence boundary does not restart from an empty pipeline
+        const bool ep_direct = direct;
+        const long long ep_row = row;
+        const long long slot = ((long long)k + b) * p.q_len + j;
+        const bool more = seq_first + ub < u_hi;
+        if (more) {
+            const int first_unit = seq_first + ub;
+            seq_first = first_unit;
+            ++b;
+            while (units_of(clamped_len(p, b)) == 0) ++b;   // empty sequences hold no units
+            set_piece(first_unit);
+            load_q();
+            if (w < n_tiles) issue_loads(w);
+        }
+
         // ---- a7: merge the four wavefronts, normalise, write (the epilogue of Algorithm 1) ----
         if constexpr (kDirect) {
 #pragma unroll
@@ -578,7 +601,6 @@ __global__ void __launch_bounds__(kThreads, 1) mla_decode_split_kernel(const Par
 
         // Statistics of the head(s) whose accumulator elements this lane holds: head r16 in all four
         // elements (transposed orientation), or heads 4g .. 4g+3, one per element (direct orientation).
-        const long long slot = ((long long)k + b) * p.q_len + j;
         f32x4 f[kWaves];
         float lse2_of[4];
         constexpr int kStatHeads = kDirect ? 4 : 1;
@@ -605,7 +627,7 @@ __global__ void __launch_bounds__(kThreads, 1) mla_decode_split_kernel(const Par
             lse2_of[i] = none ? -INFINITY : m_tot + __builtin_amdgcn_logf(l_tot);   // v_log_f32 is log2
         }
 
-        float *dst = direct ? p.out + row * kHeads * kDv : p.part_out + slot * kHeads * kDv;
+        float *dst = ep_direct ? p.out + ep_row * kHeads * kDv : p.part_out + slot * kHeads * kDv;
         // wavefront w finishes value tiles 8w .. 8w+7
 #pragma unroll
         for (int c = 0; c < kDvTiles / kWaves; ++c) {
@@ -627,19 +649,13 @@ __global__ void __launch_bounds__(kThreads, 1) mla_decode_split_kernel(const Par
 #pragma unroll
             for (int i = 0; i < kStatHeads; ++i) {
                 const int hd = kDirect ? 4 * g + i : r16;
-                if (direct) p.lse[row * kHeads + hd] = lse2_of[i] * 0.6931471805599453f;
+                if (ep_direct) p.lse[ep_row * kHeads + hd] = lse2_of[i] * 0.6931471805599453f;
                 else p.part_lse[slot * kHeads + hd] = lse2_of[i];
             }
         }
 
-        // next sequence this workgroup is bound to: the following one with at least one unit
-        cur_unit = seq_first + ub;
-        if (cur_unit < u_hi) {
-            __syncthreads();          // the tiles are overwritten next; everyone must be done reading them
-            seq_first += ub;
-            ++b;
-            while (units_of(clamped_len(p, b)) == 0) ++b;   // empty sequences hold no units
-        }
+        if (!more) break;
+        __syncthreads();              // the tiles are overwritten next; everyone must be done reading them
     }
 }
 
