@@ -78,6 +78,17 @@ def test_many_short_sequences(oracle, num_wg):
     _check(out, lse, ref_o, ref_l, label="many_short num_wg=%s" % num_wg)
 
 
+def test_one_very_long_sequence(oracle):
+    """A single sequence of 300,001 rows shared by every workgroup (176 pieces for the combine
+    kernel to merge: more than one batch of its loads), next to a one-row sequence."""
+    q, kv, l = inputs.make_inputs(2, 300001, [300001, 1], seed=111, poison_tail=True)
+    ref_o, ref_l = _oracle(oracle, q, kv, l)
+    for nwg in (None, 1000):
+        print("case very_long num_wg", nwg, flush=True)
+        out, lse = _run(q, kv, l, num_wg=nwg)
+        _check(out, lse, ref_o, ref_l, label="very_long num_wg=%s" % nwg)
+
+
 def test_empty_and_full_sequences(oracle):
     lens = [0, 384, 0, 1]
     q, kv, l = inputs.make_inputs(4, 384, lens, seed=102, poison_tail=True)
