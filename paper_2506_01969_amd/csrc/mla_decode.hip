@@ -3,7 +3,8 @@
 // Problem (paper Section 3.1, decoding setup of Section 4.1): for every sequence b and each of
 // 16 heads, one query row of 576 bf16 attends over N_b latent KV rows of 576 bf16 shared by all
 // heads; V is the first 512 columns of the same row.  out = softmax(scale * q K^T) V, plus the
-// log-sum-exp of the scaled scores (the L of Algorithm 1's last step).
+// log-sum-exp of the scaled scores (the L of Algorithm 1's last step).  Variants of the same
+// kernel take fp16 inputs and several query tokens per sequence (template parameters below).
 //
 // Orientation.  Both contractions run in the transposed form of equations (1)-(4):
 //     S^T = K Q^T   (tokens on the MFMA M axis, heads on N, contraction over the 576 dims)
@@ -18,20 +19,20 @@
 // (a sequence of N tokens holds ceil(N/128) units).  The grid is persistent: workgroup k of G
 // takes the contiguous unit range [k*U/G, (k+1)*U/G) of that stream, whatever the lengths are,
 // so ragged batches are balanced to one unit and every workgroup streams the same amount.
-// A range may cross sequence boundaries; each (workgroup, sequence) piece is a "segment" and ends
-// with its own epilogue.  Every workgroup derives the partition from cache_seqlens on the device
+// A range may cross sequence boundaries; each (workgroup, sequence) part of it is a "piece" and
+// ends with its own epilogue (the next piece's first loads are issued before that epilogue).  Every workgroup derives the partition from cache_seqlens on the device
 // (one vector load and a wave scan), so the host never needs the lengths.  The assignment is
 // static: results are bit-identical from run to run.
 //
 // Each wavefront is an independent online-softmax worker (the m / l / rescale recurrence of
-// Algorithm 1) over every 4th 32-token tile of the segment, with a
-// private LDS tile, so the main loop has no barrier.  A tile is fetched with 16-byte coalesced
+// Algorithm 1) over every 4th 32-token tile of the piece, with a private LDS tile, so the main
+// loop has no barrier.  A tile is fetched with 16-byte coalesced
 // global loads into registers (in flight while the previous tile is being computed; each register
 // is refilled with its piece of the next tile the moment it has been copied to LDS), written
 // once to LDS, and read twice from LDS: as the K operand (ds_read_b128) and, through the
 // transposing LDS read ds_read_b64_tr_b16, as the V^T operand.  The four wavefronts of a
-// workgroup merge their (m, l, O) through LDS at the end of the segment; a sequence
-// shared by several workgroups is finished by the combine kernel.
+// workgroup merge their (m, l, O) through LDS at the end of the piece; a sequence shared by
+// several workgroups is finished by the combine kernel.
 //
 // P is fed to the second MFMA as a two-term bf16 split (hi + lo): a single bf16 rounding of P
 // costs ~2^-9 relative error per term, which is outside the 1e-4 RMSE bound at short KV.
@@ -213,7 +214,7 @@ __device__ __forceinline__ void rescale_accumulators(f32x4 (&o)[kDvTiles], f32x4
 }
 
 // Main kernel (steps a0-a7 of the hot path): persistent grid, workgroup k streams its share of
-// the unit stream segment by segment.
+// the unit stream piece by piece.
 // kTeam: several query tokens per sequence, i.e. several workgroups read every KV row.
 //
 // kDirect = false is the transposed orientation of equations (1)-(4) described at the top of this
