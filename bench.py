@@ -156,6 +156,17 @@ def main():
     ms_per_step = wall / args.steps * 1e3
     tbps = alg_bytes / (ms_per_step * 1e-3) / 1e12
 
+    # ---- whole call again, each call bracketed by events on the launch stream: the spread ----------
+    evw = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
+    for i in range(args.steps):
+        evw[i][0].record()
+        step(i)
+        evw[i][1].record()
+    torch.cuda.synchronize()
+    call_us = sorted(a.elapsed_time(b) * 1e3 for a, b in evw)
+    call_stats = {"median_us": call_us[len(call_us) // 2], "min_us": call_us[0],
+                  "p90_us": call_us[min(len(call_us) - 1, (len(call_us) * 9) // 10)]}
+
     # ---- main kernel alone, events on the launch stream (torch's current stream) ---------------
     ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
     for i in range(min(args.warmup, 5)):
@@ -210,7 +221,8 @@ def main():
                                    else "ragged uniform[%d,%d]" % cfg["ragged"]),
                    "total_kv_tokens": int(lens.sum()), "algorithmic_bytes_per_call": alg_bytes,
                    "algorithmic_flops_per_call": alg_flops, "workgroups": nwg_used,
-                   "kv_buffers_rotated": n_buf, "orientation": args.orientation, "hbm_peak_frac_whole_call": tbps * 1e3 / HBM_PEAK_GBPS,
+                   "kv_buffers_rotated": n_buf, "orientation": args.orientation,
+                   "call_event_timing": call_stats, "hbm_peak_frac_whole_call": tbps * 1e3 / HBM_PEAK_GBPS,
                    "tflops_whole_call": alg_flops / (ms_per_step * 1e-3) / 1e12},
         "roofline": {"bound": "hbm", "kernel": "mla_decode_split_kernel", "achieved": achieved_gbps,
                      "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": achieved_gbps / HBM_PEAK_GBPS, "traffic": traffic,
