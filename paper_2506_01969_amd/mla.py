@@ -2,7 +2,7 @@
 
 Every step of the computation runs inside ``libmla_decode.so``; torch is used for device
 memory and the current stream, nothing else.  There is no fallback: if the library is
-missing or fails to load, importing callers get an error.
+not built it is built (hipcc), and if that or the load fails, callers get an error.
 """
 from __future__ import annotations
 
@@ -33,12 +33,14 @@ class MlaError(RuntimeError):
 
 
 def lib():
-    """Load ``libmla_decode.so`` (built by ``paper_2506_01969_amd.build``); raises if absent."""
+    """Load ``libmla_decode.so``.  What is built is loaded as it is; only when nothing is built is
+    the build step (``paper_2506_01969_amd.build``, hipcc) run first.  Any failure raises: there is
+    no other implementation to fall back to."""
     global _lib
     if _lib is None:
         if not os.path.exists(LIB_PATH):
-            raise RuntimeError(
-                "%s not found: run `python -c 'import __graft_entry__ as g; g.build()'` first" % LIB_PATH)
+            from . import build as _build
+            _build.build_library()
         L = ctypes.CDLL(LIB_PATH)
         vp, ci, sz = ctypes.c_void_p, ctypes.c_int, ctypes.c_size_t
         szp, cip = ctypes.POINTER(ctypes.c_size_t), ctypes.POINTER(ctypes.c_int)
