@@ -110,6 +110,19 @@ def test_lengths_are_clamped_on_the_device(oracle):
     _check(out, lse, ref_o, ref_l, label="clamp")
 
 
+@pytest.mark.parametrize("scale", [0.0, -0.05, 0.5])
+def test_unusual_scales(oracle, scale):
+    """scale 0 gives the plain mean of V and lse = ln N; a negative scale prefers the smallest
+    scores; a large one makes the softmax nearly one-hot (scores of standard deviation 12)."""
+    q, kv, l = inputs.make_inputs(3, 700, [700, 129, 5], seed=112, poison_tail=True)
+    ref_o, ref_l = _oracle(oracle, q, kv, l, scale=scale)
+    print("case scale", scale, flush=True)
+    out, lse = _run(q, kv, l, scale=scale)
+    _check(out, lse, ref_o, ref_l, tight=(scale != 0.5), label="scale=%g" % scale)
+    if scale == 0.0:
+        assert abs(lse[0, 0] - math.log(700)) < 1e-5
+
+
 def test_batch_stride_larger_than_sequence(oracle):
     dev = _dev()
     q, kv, l = inputs.make_inputs(3, 300, [300, 17, 222], seed=104)
