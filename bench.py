@@ -130,7 +130,8 @@ def main():
     for _ in range(n_buf - 1):
         kvs.append(kvs[0].clone())
     nwg = args.workgroups or None
-    need, nwg_used = mla.mla_decode_workspace_size(batch * args.q_len, 16, max_seqlen, args.workgroups)
+    need, _ = mla.mla_decode_workspace_size(batch * args.q_len, 16, max_seqlen, args.workgroups)
+    nwg_used = args.workgroups or mla.mla_decode_planned_workgroups(args.q_len)
     ws = torch.empty((need,), dtype=torch.uint8, device=dev)
     out = torch.empty((batch, args.q_len, 16, 512), dtype=torch.float32, device=dev)
     lse = torch.empty((batch, args.q_len, 16), dtype=torch.float32, device=dev)

@@ -55,7 +55,10 @@ typedef enum {
  * queried: the automatic plan is a persistent workgroup on 11 of every 16 compute
  * units, which is where HBM saturates).
  * The size depends only on (batch, number of workgroups), never on the
- * per-sequence lengths, which live on the device.
+ * per-sequence lengths, which live on the device: one partial result (16 x 512 fp32 plus
+ * 16 log-sum-exps) for 2 * num_workgroups + batch + MLA_MAX_Q_LEN slots; a workgroup
+ * writes one partial result per sequence it touches and per query token it works for,
+ * at most two tokens (see mla_decode_typed()).
  *
  *   batch                >= 1 sequences
  *   num_heads            must be MLA_NUM_HEADS
@@ -143,9 +146,12 @@ mla_status_t mla_decode_ex(const void *q, const void *kv_cache, int64_t kv_batch
  *            token j (0-based) attends to rows [0, cache_seqlens[b] - (q_len - 1 - j)); a token
  *            left with no row yields out = 0 and lse = -inf.
  *          The workspace must have the size mla_decode_workspace_size() returns for
- *          batch * q_len in place of batch.  The workgroups run in teams of q_len that take the
- *          same KV rows at the same time, one query token each, so a row comes in from HBM once
- *          and the other readers are served by the memory-side cache.
+ *          batch * q_len in place of batch.  With q_len >= 2 a workgroup works for two query
+ *          tokens (two of its four wavefronts each) on the KV rows it streams, so a row is
+ *          fetched once for both; with more than two tokens, ceil(q_len / 2) such workgroups
+ *          form a team that takes the same KV rows at the same time, so that a row comes in
+ *          from HBM once and the other readers are served by the memory-side cache.  The
+ *          automatic plan then uses every compute unit (mla_decode_planned_workgroups()).
  * All other arguments, layouts and error behaviour are those of mla_decode_ex().
  */
 #define MLA_DTYPE_BF16 0
@@ -156,6 +162,14 @@ mla_status_t mla_decode_typed(const void *q, const void *kv_cache, int64_t kv_ba
                               int max_seqlen_kv, int dtype, float scale, float *out, float *lse,
                               void *workspace, size_t workspace_bytes, int num_workgroups,
                               int flags, void *stream);
+
+/*
+ * The number of workgroups the automatic plan (num_workgroups == 0) launches on the current HIP
+ * device for q_len query tokens per sequence: 11 of every 16 compute units for one token, every
+ * compute unit for more.  Host only.  q_len outside 1 .. MLA_MAX_Q_LEN is
+ * MLA_ERR_UNSUPPORTED_SHAPE, a NULL pointer MLA_ERR_INVALID_ARG.
+ */
+mla_status_t mla_decode_planned_workgroups(int q_len, int *num_workgroups);
 
 /* Static string for a status code (never NULL). */
 const char *mla_status_string(mla_status_t status);

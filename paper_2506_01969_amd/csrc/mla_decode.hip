@@ -20,9 +20,10 @@
 // takes the contiguous unit range [k*U/G, (k+1)*U/G) of that stream, whatever the lengths are,
 // so ragged batches are balanced to one unit and every workgroup streams the same amount.
 // A range may cross sequence boundaries; each (workgroup, sequence) part of it is a "piece" and
-// ends with its own epilogue (the next piece's first loads are issued before that epilogue).  Every workgroup derives the partition from cache_seqlens on the device
-// (one vector load and a wave scan), so the host never needs the lengths.  The assignment is
-// static: results are bit-identical from run to run.
+// ends with its own epilogue (the next piece's first loads are issued before that epilogue).
+// Every workgroup derives the partition from cache_seqlens on the device (one vector load and a
+// wave scan), so the host never needs the lengths.  The assignment is static: results are
+// bit-identical from run to run.
 //
 // Each wavefront is an independent online-softmax worker (the m / l / rescale recurrence of
 // Algorithm 1) over every 4th 32-token tile of the piece, with a private LDS tile, so the main
@@ -33,6 +34,16 @@
 // transposing LDS read ds_read_b64_tr_b16, as the V^T operand.  The four wavefronts of a
 // workgroup merge their (m, l, O) through LDS at the end of the piece; a sequence shared by
 // several workgroups is finished by the combine kernel.
+//
+// Several query tokens per sequence (speculative / multi-token decoding, kShare = 2).  A workgroup
+// takes two tokens: wavefronts 0 and 2 work for the first, 1 and 3 for the second.  Every
+// wavefront still stages its own tiles, and then takes its own tile and its neighbour's (0 <-> 1,
+// 2 <-> 3), read from the neighbour's LDS region, for its own token.  A KV row is thus fetched
+// once for both tokens, every wavefront keeps a tile of its own in flight as with one token, and
+// only the LDS reads and the MFMA work double.  Two workgroup barriers per round (neighbour's
+// tile written / everyone done reading) replace the barrier-free loop.  More than two tokens are
+// spread over teams of ceil(q_len / 2) such workgroups that stream the same KV rows at the same
+// time behind one L2 cache.
 //
 // P is fed to the second MFMA as a two-term bf16 split (hi + lo): a single bf16 rounding of P
 // costs ~2^-9 relative error per term, which is outside the 1e-4 RMSE bound at short KV.
@@ -63,6 +74,7 @@ constexpr int kDvTiles = kDv / 16;           // 32 output tiles of 16 value colu
 constexpr int kStatsOff = kWaves * kWaveLds; // m and l of the 4 wavefronts live after the tiles
 constexpr int kRescaleOff = kStatsOff + 2 * kWaves * kHeads * 4;  // 2 KB per wavefront, cold rescale path
 constexpr int kLdsBytes = kRescaleOff + kWaves * 2048;
+static_assert(kLdsBytes <= 160 * 1024, "LDS of one compute unit");
 constexpr int kUnit = kWaves * kTile;          // 128 tokens: the scheduling unit (one tile per wavefront)
 static_assert(kUnit == MLA_UNIT_TOKENS, "header and kernel disagree on the scheduling unit");
 constexpr int kCombineThreads = 128;
@@ -215,7 +227,9 @@ __device__ __forceinline__ void rescale_accumulators(f32x4 (&o)[kDvTiles], f32x4
 
 // Main kernel (steps a0-a7 of the hot path): persistent grid, workgroup k streams its share of
 // the unit stream piece by piece.
-// kTeam: several query tokens per sequence, i.e. several workgroups read every KV row.
+// kShare: query tokens per workgroup (1, or 2 with the wavefront pairs described at the top).
+// kTeam: several workgroups read every KV row (more query tokens than one workgroup takes), so the
+// loads are not marked as streaming.
 //
 // kDirect = false is the transposed orientation of equations (1)-(4) described at the top of this
 // file.  kDirect = true is the original orientation of Section 3.1, kept for comparison:
@@ -225,8 +239,10 @@ __device__ __forceinline__ void rescale_accumulators(f32x4 (&o)[kDvTiles], f32x4
 // lane with ONE token and four heads: the softmax maximum of a head needs a reduction across 16
 // lanes, every lane carries the running statistics of four heads, and P has to be transposed
 // across lanes (through 2 KB of LDS) before it can enter the second product.
-template <int kDtype, bool kTeam, bool kDirect>
+template <int kDtype, bool kTeam, bool kDirect, int kShare>
 __global__ void __launch_bounds__(kThreads, 1) mla_decode_split_kernel(const Params p) {
+    static_assert(kShare == 1 || (kShare == 2 && !kDirect), "tokens per workgroup");
+    constexpr int kGroups = kWaves / kShare;      // wavefronts that work for the same query token
     extern __shared__ __attribute__((aligned(16))) char smem[];
 
     const int tid = threadIdx.x;
@@ -236,15 +252,19 @@ __global__ void __launch_bounds__(kThreads, 1) mla_decode_split_kernel(const Par
     const int g = l >> 4;         // MFMA k-group (0..3)
 
     // ---- a0 on the device: this workgroup's range of the unit stream -------------------------
-    // With q_len query tokens per sequence, q_len workgroups form a team: all of them take the
-    // same share of the unit stream, each for its own query token, so they stream the same KV rows
-    // at the same time and only the first to ask brings a row in from HBM; the others find it in
-    // the L2 cache (they run a little faster for it and so never fall far behind).  The members of
-    // a team are a multiple of 8 workgroup ids apart: workgroups are dealt to the 8 XCDs in turn
-    // and each XCD has its own L2, so this puts a team behind one L2.
-    const int team_stride = gridDim.x / p.q_len;         // number of teams, rounded up to a multiple of 8
-    const int j = blockIdx.x / team_stride;              // query token of this workgroup
-    const int k = blockIdx.x - j * team_stride;          // team
+    // With more than kShare query tokens per sequence, ceil(q_len / kShare) workgroups form a team:
+    // all of them take the same share of the unit stream, each for its own query tokens, so they
+    // stream the same KV rows at the same time and only the first to ask brings a row in from HBM;
+    // the others find it in the L2 cache (they run a little faster for it and so never fall far
+    // behind).  The members of a team are a multiple of 8 workgroup ids apart: workgroups are
+    // dealt to the 8 XCDs in turn and each XCD has its own L2, so this puts a team behind one L2.
+    const int members = (p.q_len + kShare - 1) / kShare; // workgroups per team
+    const int team_stride = gridDim.x / members;         // number of teams, rounded up to a multiple of 8
+    const int jt = blockIdx.x / team_stride;             // member of the team
+    const int k = blockIdx.x - jt * team_stride;         // team
+    const int tk = w & (kShare - 1);                     // this wavefront's query token within the workgroup
+    const int j = jt * kShare + tk;                      // query token of this wavefront (scalar)
+    const bool has_token = j < p.q_len;                  // odd q_len: the last wavefront pair has one token only
     int total_units, unused;
     unit_sums(p, l, 0, total_units, unused);
     // never more workgroups than units: every active workgroup then holds at least one unit
@@ -265,12 +285,36 @@ __global__ void __launch_bounds__(kThreads, 1) mla_decode_split_kernel(const Par
         const int boundary = 72 * ((r * 64) / 72 + 1) - r * 64;     // 72, 8, 16, ..., 56, 64
         wr_flat[r] = my + l * 16 + (l >= boundary ? 16 : 0);
     }
-    const char *rd_k = my + r16 * kLdsRow + g * 16;       // K operand: token r16 (+16), chunk 4*kk + g
+    // With two query tokens a few more values are live across the tile loop and the nine addresses
+    // would push others out of the register file (a value reloaded from scratch memory inside the
+    // loop has to wait for every KV load issued before it).  There the address is worked out at
+    // each write from the lane number, which costs two vector instructions per 1 KB written.
+    auto wr_addr = [&](int i, int lane) -> char * {
+        if constexpr (kShare == 1) {
+            return wr_flat[i % 9];
+        } else {
+            const int r = i % 9;
+            const int boundary = 72 * ((r * 64) / 72 + 1) - r * 64;
+            return my + lane * 16 + (lane >= boundary ? 16 : 0);
+        }
+    };
+    // Transposed orientation: MFMA row r of a score block is not token r of the tile's 16 but token
+    // rho(r) = 2 r mod 16 + (r >= 8), i.e. rows 0..7 are the even tokens and rows 8..15 the odd ones.
+    // The order of the tokens inside a tile is free (both products sum over them); this one lets
+    // the transposing V^T reads below, whose first 32 lanes touch the tokens of MFMA rows 0..7,
+    // fall on eight LDS rows whose bank ranges (row stride 292 words: 72 words apart for every
+    // second row) tile the 64 banks exactly.  With the identity order the eighth row wraps onto
+    // the first row's banks and every such read takes two passes.
+    const int k_row = kDirect ? r16 : ((2 * r16) & 15) + (r16 >> 3);
+    const int k_off = k_row * kLdsRow + g * 16;           // K operand: token k_row (+16), chunk 4*kk + g
     // V^T operand through the transposing read: within each 16-lane group, lane j points at
     // row j/4, columns 4*(j%4)..+3 of a 4x16 block and receives column j, rows 0..3.
     // Tokens of the two reads, in the order of the other operand's 8 k-values: transposed
-    // orientation 4g..4g+3 and 16+4g..; direct orientation 8g..8g+3 and 8g+4..
-    const char *rd_v = my + ((kDirect ? 8 : 4) * g + (r16 >> 2)) * kLdsRow + (r16 & 3) * 8;
+    // orientation rho(4g) .. rho(4g+3) and 16 more; direct orientation 8g..8g+3 and 8g+4..
+    // token of score-block row 4g + i (this lane's elements i = 0..3): rho(4g + i) = tok0 + 2 i
+    const int tok0 = 8 * (g & 1) + (g >> 1);
+    const int v_row = kDirect ? 8 * g + (r16 >> 2) : tok0 + 2 * (r16 >> 2);
+    const int v_off = v_row * kLdsRow + (r16 & 3) * 8;
     constexpr int kVSecond = (kDirect ? 4 : 16) * kLdsRow;
     // direct orientation: P crosses lanes as fp32 [16 heads][32 tokens], in the rescale path's slot
     float *p_tr = reinterpret_cast<float *>(smem + kRescaleOff + w * 2048);
@@ -279,7 +323,7 @@ __global__ void __launch_bounds__(kThreads, 1) mla_decode_split_kernel(const Par
     const unsigned lane16 = (unsigned)l * 16;               // global-load lane offsets (bytes)
 
     // ---- the piece being worked on (this team's units of one sequence) -----------------------
-    int n, ub, t_begin, t_end, n_tiles;
+    int n, ub, t_begin, t_end, n_tiles;   // t_end: end of what this wavefront's token sees; n_tiles: tiles staged
     bool direct;
     const char *kv_b;
     long long row;                    // row of q, out and lse
@@ -289,8 +333,10 @@ __global__ void __launch_bounds__(kThreads, 1) mla_decode_split_kernel(const Par
         const int u_begin = first_unit - seq_first;
         const int u_end = min(u_hi - seq_first, ub);           // > u_begin
         t_begin = u_begin * kUnit;
-        t_end = min(visible_len(p, n, j), u_end * kUnit);      // may be <= t_begin: nothing visible here
-        n_tiles = t_end > t_begin ? (t_end - t_begin + kTile - 1) / kTile : 0;
+        t_end = has_token ? min(visible_len(p, n, j), u_end * kUnit) : 0;   // may be <= t_begin: nothing visible here
+        // the tiles staged cover what the last token of this workgroup sees
+        const int stage_end = kShare > 1 ? min(visible_len(p, n, min(jt * kShare + kShare - 1, p.q_len - 1)), u_end * kUnit) : t_end;
+        n_tiles = stage_end > t_begin ? (stage_end - t_begin + kTile - 1) / kTile : 0;
         direct = (u_begin == 0 && u_end == ub);                // this team covers the whole sequence
         kv_b = p.kv + (long long)b * p.kv_batch_bytes;
         row = (long long)b * p.q_len + j;
@@ -344,10 +390,11 @@ __global__ void __launch_bounds__(kThreads, 1) mla_decode_split_kernel(const Par
         f32x4 l4 = {0.f, 0.f, 0.f, 0.f};
 
         bool first_tile = true;
-        while (cur < n_tiles) {
-            const int tb = t_begin + cur * kTile;
 
-            // ---- a2: registers -> private LDS tile ----------------------------------------
+        // ---- a2: registers -> private LDS tile --------------------------------------------
+        auto stage_tile = [&]() {
+            int lane = l;
+            if constexpr (kShare > 1) asm volatile("" : "+v"(lane));   // keeps the addresses from being hoisted out of the loop
             // chunk c = 64 i + l goes to row c / 72, column chunk c % 72: byte 16 (c + c / 72)
             // Each piece's register is refilled with the same piece of the next tile as soon as it
             // has been written to LDS, so this wavefront keeps 35 requests in flight at all times
@@ -359,7 +406,7 @@ __global__ void __launch_bounds__(kThreads, 1) mla_decode_split_kernel(const Par
                 const char *tile_base = kv_b + (long long)ntb * kRowBytes;
 #pragma unroll
                 for (int i = 0; i < kTileLoads; ++i) {
-                    *reinterpret_cast<u32x4 *>(wr_flat[i % 9] + i * 1024 + ((i * 64) / 72) * 16) = st[i];
+                    *reinterpret_cast<u32x4 *>(wr_addr(i, lane) + i * 1024 + ((i * 64) / 72) * 16) = st[i];
                     const int piece = min(i * 1024, last_chunk16);          // scalar
                     st[i] = load_stream16<kTeam>(tile_base + piece, min(lane16, (unsigned)(last_chunk16 - piece)));
                 }
@@ -371,9 +418,13 @@ __global__ void __launch_bounds__(kThreads, 1) mla_decode_split_kernel(const Par
             } else {
 #pragma unroll
                 for (int i = 0; i < kTileLoads; ++i)
-                    *reinterpret_cast<u32x4 *>(wr_flat[i % 9] + i * 1024 + ((i * 64) / 72) * 16) = st[i];
+                    *reinterpret_cast<u32x4 *>(wr_addr(i, lane) + i * 1024 + ((i * 64) / 72) * 16) = st[i];
             }
+        };
 
+        // ---- a3 to a6 on the 32 rows from row tb of the sequence that sit in an LDS tile (rd_k, rd_v:
+        // this lane's read addresses in that tile), for this wavefront's query token
+        auto process_tile = [&](const char *rd_k, const char *rd_v, const int tb) {
             // ---- a3: S^T = K Q^T for tokens 0..15 and 16..31 of the tile (equation (1)) --
             // LDS reads run kKAhead k-steps ahead of the MFMAs that consume them.
             f32x4 s0 = {0.f, 0.f, 0.f, 0.f}, s1 = {0.f, 0.f, 0.f, 0.f};
@@ -461,14 +512,14 @@ __global__ void __launch_bounds__(kThreads, 1) mla_decode_split_kernel(const Par
                     pr[4 + i] = hi4[i];
                 }
             } else {
-            // this lane now holds, for head r16, tokens tb + 4g + i (s0[i]) and tb + 16 + 4g + i (s1[i])
+            // this lane now holds, for head r16, tokens tb + tok0 + 2i (s0[i]) and 16 more (s1[i])
 
             // ---- a4: scale (base-2 domain) and mask the tail ------------------------------
             float x[8];
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
-                x[i] = (tb + 4 * g + i < t_end) ? s0[i] * p.scale_log2e : -INFINITY;
-                x[4 + i] = (tb + 16 + 4 * g + i < t_end) ? s1[i] * p.scale_log2e : -INFINITY;
+                x[i] = (tb + tok0 + 2 * i < t_end) ? s0[i] * p.scale_log2e : -INFINITY;
+                x[4 + i] = (tb + 16 + tok0 + 2 * i < t_end) ? s1[i] * p.scale_log2e : -INFINITY;
             }
 
             // ---- a5: online softmax (Algorithm 1: m, l update) -----------------------------
@@ -552,9 +603,37 @@ __global__ void __launch_bounds__(kThreads, 1) mla_decode_split_kernel(const Par
                     if (ct + kVAhead < kDvTiles) __builtin_amdgcn_sched_group_barrier(kSchedDsRead, 2, 1);
                 }
             }
+        };
 
-            cur = nxt;
-            nxt += kWaves;
+        if constexpr (kShare == 1) {
+            while (cur < n_tiles) {
+                stage_tile();
+                process_tile(my + k_off, my + v_off, t_begin + cur * kTile);
+                cur = nxt;
+                nxt += kWaves;
+            }
+        } else {
+            // Two wavefronts, one per query token, share the tiles that each of them stages: every
+            // wavefront takes its own tile first and then its neighbour's tile, for its own token.  Each
+            // KV row is fetched once for both tokens and every wavefront still keeps a tile of its own
+            // in flight.  The barriers are reached by all wavefronts the same number of times
+            // (n_tiles is the same for all of them).
+            for (int base = 0; base < n_tiles; base += kWaves) {
+                if (cur < n_tiles) stage_tile();
+#pragma unroll
+                for (int sh = 0; sh < kShare; ++sh) {
+                    if (sh == 1) __syncthreads();                    // the neighbours' tiles are in LDS
+                    const int ws = (w & ~(kShare - 1)) | ((tk + sh) & (kShare - 1));
+                    const int tb = t_begin + (base + ws) * kTile;
+                    if (base + ws < n_tiles && tb < t_end) {         // staged, and visible to this token
+                        const char *tile = smem + ws * kWaveLds;
+                        process_tile(tile + k_off, tile + v_off, tb);
+                    }
+                }
+                __syncthreads();                                     // before the tiles are overwritten
+                cur = nxt;
+                nxt += kWaves;
+            }
         }
 
         // ---- the next piece's q and first tile go in flight before this piece's epilogue, so a
@@ -602,26 +681,27 @@ __global__ void __launch_bounds__(kThreads, 1) mla_decode_split_kernel(const Par
 
         // Statistics of the head(s) whose accumulator elements this lane holds: head r16 in all four
         // elements (transposed orientation), or heads 4g .. 4g+3, one per element (direct orientation).
-        f32x4 f[kWaves];
+        // The wavefronts merged are those of this wavefront's token: tk, tk + kShare, ...
+        f32x4 f[kGroups];
         float lse2_of[4];
         constexpr int kStatHeads = kDirect ? 4 : 1;
 #pragma unroll
         for (int i = 0; i < kStatHeads; ++i) {
             const int hd = kDirect ? 4 * g + i : r16;
-            float m_tot = stat_m[hd];
+            float m_tot = stat_m[tk * kHeads + hd];
 #pragma unroll
-            for (int ww = 1; ww < kWaves; ++ww) m_tot = fmaxf(m_tot, stat_m[ww * kHeads + hd]);
+            for (int ww = 1; ww < kGroups; ++ww) m_tot = fmaxf(m_tot, stat_m[(tk + ww * kShare) * kHeads + hd]);
             const bool none = (m_tot == -INFINITY);      // the whole workgroup drew no tile of this sequence
-            float fw[kWaves];
+            float fw[kGroups];
             float l_tot = 0.f;
 #pragma unroll
-            for (int ww = 0; ww < kWaves; ++ww) {
-                fw[ww] = none ? 0.f : __builtin_amdgcn_exp2f(stat_m[ww * kHeads + hd] - m_tot);   // 0 for an idle wavefront
-                l_tot += fw[ww] * stat_l[ww * kHeads + hd];
+            for (int ww = 0; ww < kGroups; ++ww) {
+                fw[ww] = none ? 0.f : __builtin_amdgcn_exp2f(stat_m[(tk + ww * kShare) * kHeads + hd] - m_tot);   // 0 for an idle wavefront
+                l_tot += fw[ww] * stat_l[(tk + ww * kShare) * kHeads + hd];
             }
             const float inv_l = none ? 0.f : 1.0f / l_tot;
 #pragma unroll
-            for (int ww = 0; ww < kWaves; ++ww) {
+            for (int ww = 0; ww < kGroups; ++ww) {
                 if constexpr (kDirect) f[ww][i] = fw[ww] * inv_l;
                 else f[ww] = f32x4{fw[ww] * inv_l, fw[ww] * inv_l, fw[ww] * inv_l, fw[ww] * inv_l};
             }
@@ -629,24 +709,25 @@ __global__ void __launch_bounds__(kThreads, 1) mla_decode_split_kernel(const Par
         }
 
         float *dst = ep_direct ? p.out + ep_row * kHeads * kDv : p.part_out + slot * kHeads * kDv;
-        // wavefront w finishes value tiles 8w .. 8w+7
+        // of its token's 32 value tiles, this wavefront finishes an equal share (8 with one token)
+        constexpr int kFinish = kDvTiles / kGroups;
 #pragma unroll
-        for (int c = 0; c < kDvTiles / kWaves; ++c) {
-            const int ct = w * (kDvTiles / kWaves) + c;
+        for (int c = 0; c < kFinish; ++c) {
+            const int ct = (w / kShare) * kFinish + c;
             f32x4 acc = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-            for (int ww = 0; ww < kWaves; ++ww) {
-                const f32x4 part = *reinterpret_cast<const f32x4 *>(smem + ww * kWaveLds + ct * 1024 + l * 16);
+            for (int ww = 0; ww < kGroups; ++ww) {
+                const f32x4 part = *reinterpret_cast<const f32x4 *>(smem + (tk + ww * kShare) * kWaveLds + ct * 1024 + l * 16);
                 acc += part * f[ww];
             }
             if constexpr (kDirect) {      // element i: head 4g + i, column 16 ct + r16
 #pragma unroll
                 for (int i = 0; i < 4; ++i) dst[(4 * g + i) * kDv + ct * 16 + r16] = acc[i];
             } else {                      // head r16, columns 16 ct + 4g .. +3; equation (4): transpose by addressing
-                *reinterpret_cast<f32x4 *>(dst + r16 * kDv + ct * 16 + g * 4) = acc;
+                if (has_token) *reinterpret_cast<f32x4 *>(dst + r16 * kDv + ct * 16 + g * 4) = acc;
             }
         }
-        if (w == 0 && (kDirect ? r16 == 0 : g == 0)) {
+        if (w < kShare && has_token && (kDirect ? r16 == 0 : g == 0)) {
 #pragma unroll
             for (int i = 0; i < kStatHeads; ++i) {
                 const int hd = kDirect ? 4 * g + i : r16;
@@ -732,11 +813,28 @@ __global__ void __launch_bounds__(kCombineThreads) mla_decode_combine_kernel(con
 
 // ---- host side ---------------------------------------------------------------------------------
 
+// Query tokens that one workgroup can take (two wavefronts per token): used when q_len >= 2.
+constexpr int kMaxShare = 2;
+
+// How q_len query tokens are spread: `share` tokens per workgroup, `members` workgroups per team
+// (all members stream the same KV rows), `teams` shares of the unit stream.
+struct Plan {
+    int share, members, teams;
+};
+
+inline Plan plan_for(int q_len, int num_wg, bool direct_orientation) {
+    Plan pl;
+    pl.share = (q_len >= 2 && !direct_orientation) ? 2 : 1;
+    pl.members = (q_len + pl.share - 1) / pl.share;
+    pl.teams = num_wg / pl.members > 0 ? num_wg / pl.members : 1;
+    return pl;
+}
+
 inline size_t workspace_bytes_for(int batch, int num_wg) {
-    // one partial slot per (workgroup, sequence) pair that can occur: slot = k + b < num_wg + batch;
-    // with q_len query tokens (batch then counts sequences x tokens) the workgroups are rounded to
-    // whole teams, at least one: at most MLA_MAX_Q_LEN more than num_wg
-    const size_t slots = (size_t)num_wg + (size_t)batch + MLA_MAX_Q_LEN;
+    // One partial slot per (team, sequence, query token) that can occur: (teams + sequences) x q_len.
+    // `batch` counts sequences x tokens.  A team is one or more workgroups and a workgroup takes at
+    // most kMaxShare tokens, so teams x q_len <= kMaxShare x num_wg, or q_len (one team) if larger.
+    const size_t slots = (size_t)kMaxShare * (size_t)num_wg + (size_t)batch + MLA_MAX_Q_LEN;
     const size_t po = slots * kHeads * kDv * sizeof(float);
     const size_t pl = slots * kHeads * sizeof(float);
     return po + ((pl + 15) & ~(size_t)15);
@@ -776,24 +874,28 @@ mla_status_t launch(const void *q, const void *kv_cache, int64_t kv_batch_stride
                     const int32_t *cache_seqlens, int batch, int q_len, int max_seqlen_kv, float scale,
                     float *out, float *lse, void *workspace, size_t workspace_bytes, int num_wg,
                     int flags, int dtype, void *stream) {
-    // teams of q_len workgroups; the workspace holds one slot per (team, sequence, query token)
-    const int teams = num_wg / q_len > 0 ? num_wg / q_len : 1;
     if (num_wg <= 0 || num_wg > kMaxWorkgroups) return MLA_ERR_INVALID_ARG;
+    const bool direct_orientation = (flags & MLA_ORIENT_DIRECT) != 0;
+    if (direct_orientation && (q_len > 1 || dtype != MLA_DTYPE_BF16)) return MLA_ERR_UNSUPPORTED_SHAPE;
+    // the workspace holds one slot per (team, sequence, query token)
+    const Plan plan = plan_for(q_len, num_wg, direct_orientation);
+    const int teams = plan.teams;
     if (workspace_bytes < workspace_bytes_for(batch * q_len, num_wg)) return MLA_ERR_WORKSPACE_TOO_SMALL;
 
     // the main kernel needs more dynamic LDS than the default limit: raise it once per device
     static std::mutex mu;
-    static bool attr_done[64][5] = {};
+    static bool attr_done[64][7] = {};
     int dev = 0;
     if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return MLA_ERR_HIP;
     typedef void (*kernel_fn)(const Params);
-    static const kernel_fn kernels[5] = {
-        mla_decode_split_kernel<MLA_DTYPE_BF16, false, false>, mla_decode_split_kernel<MLA_DTYPE_F16, false, false>,
-        mla_decode_split_kernel<MLA_DTYPE_BF16, true, false>, mla_decode_split_kernel<MLA_DTYPE_F16, true, false>,
-        mla_decode_split_kernel<MLA_DTYPE_BF16, false, true>};
-    const bool direct_orientation = (flags & MLA_ORIENT_DIRECT) != 0;
-    if (direct_orientation && (q_len > 1 || dtype != MLA_DTYPE_BF16)) return MLA_ERR_UNSUPPORTED_SHAPE;
-    const int variant = direct_orientation ? 4 : (q_len > 1 ? 2 : 0) + (dtype == MLA_DTYPE_F16 ? 1 : 0);
+    static const kernel_fn kernels[7] = {
+        mla_decode_split_kernel<MLA_DTYPE_BF16, false, false, 1>, mla_decode_split_kernel<MLA_DTYPE_F16, false, false, 1>,
+        mla_decode_split_kernel<MLA_DTYPE_BF16, true, false, 2>,  mla_decode_split_kernel<MLA_DTYPE_F16, true, false, 2>,
+        mla_decode_split_kernel<MLA_DTYPE_BF16, false, true, 1>,
+        mla_decode_split_kernel<MLA_DTYPE_BF16, false, false, 2>, mla_decode_split_kernel<MLA_DTYPE_F16, false, false, 2>};
+    // 0, 1: one query token; 2, 3: teams of workgroups with two tokens each; 4: one token, direct
+    // orientation; 5, 6: two tokens, one workgroup per team
+    const int variant = direct_orientation ? 4 : (plan.share == 1 ? 0 : plan.members > 1 ? 2 : 5) + (dtype == MLA_DTYPE_F16 ? 1 : 0);
     const kernel_fn split_fn = kernels[variant];
     {
         std::lock_guard<std::mutex> lock(mu);
@@ -822,8 +924,8 @@ mla_status_t launch(const void *q, const void *kv_cache, int64_t kv_batch_stride
 
     hipStream_t hs = static_cast<hipStream_t>(stream);
     if (flags & MLA_PHASE_SPLIT) {
-        const int team_stride = q_len > 1 ? (teams + 7) / 8 * 8 : teams;   // see the kernel: a team behind one L2
-        hipLaunchKernelGGL(split_fn, dim3(team_stride * q_len), dim3(kThreads), kLdsBytes, hs, p);
+        const int team_stride = plan.members > 1 ? (teams + 7) / 8 * 8 : teams;   // see the kernel: a team behind one L2
+        hipLaunchKernelGGL(split_fn, dim3(team_stride * plan.members), dim3(kThreads), kLdsBytes, hs, p);
         if (hipGetLastError() != hipSuccess) return MLA_ERR_HIP;
     }
     if (flags & MLA_PHASE_COMBINE) {
@@ -909,6 +1011,12 @@ mla_status_t mla_decode(const void *q, const void *kv_cache, int64_t kv_batch_st
                         void *stream) {
     return mla_decode_ex(q, kv_cache, kv_batch_stride, cache_seqlens, batch, num_heads, max_seqlen_kv, scale,
                          out, lse, workspace, workspace_bytes, 0, MLA_PHASE_SPLIT | MLA_PHASE_COMBINE, stream);
+}
+
+mla_status_t mla_decode_planned_workgroups(int q_len, int *num_workgroups) {
+    if (!num_workgroups) return MLA_ERR_INVALID_ARG;
+    if (q_len < 1 || q_len > kMaxQLen) return MLA_ERR_UNSUPPORTED_SHAPE;
+    return planned_workgroups(q_len, num_workgroups, nullptr);
 }
 
 const char *mla_status_string(mla_status_t status) {

@@ -54,6 +54,8 @@ def lib():
         L.mla_decode_typed.argtypes = [vp, vp, ctypes.c_int64, vp, ci, ci, ci, ci, ci, ctypes.c_float, vp, vp,
                                        vp, sz, ci, ci, vp]
         L.mla_decode_typed.restype = ci
+        L.mla_decode_planned_workgroups.argtypes = [ci, cip]
+        L.mla_decode_planned_workgroups.restype = ci
         L.mla_status_string.argtypes = [ci]
         L.mla_status_string.restype = ctypes.c_char_p
         _lib = L
@@ -68,6 +70,15 @@ def mla_decode_workspace_size(batch, num_heads, max_seqlen_kv, num_workgroups=0)
     if st != MLA_OK:
         raise MlaError(st, "mla_decode_workspace_size")
     return nbytes.value, used.value
+
+
+def mla_decode_planned_workgroups(q_len=1):
+    """Workgroups the automatic plan launches on the current device for q_len query tokens."""
+    n = ctypes.c_int(0)
+    st = lib().mla_decode_planned_workgroups(q_len, ctypes.byref(n))
+    if st != MLA_OK:
+        raise MlaError(st, "mla_decode_planned_workgroups")
+    return n.value
 
 
 def _check_tensors(q, kv_cache, cache_seqlens):

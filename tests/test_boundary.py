@@ -20,7 +20,8 @@ def _declared_functions():
 
 def test_library_exports_every_declared_symbol():
     names = _declared_functions()
-    assert {"mla_decode", "mla_decode_ex", "mla_decode_workspace_size", "mla_status_string"} <= set(names)
+    assert {"mla_decode", "mla_decode_ex", "mla_decode_typed", "mla_decode_workspace_size",
+            "mla_decode_planned_workgroups", "mla_status_string"} <= set(names)
     lib = mla.lib()
     for n in names:
         assert hasattr(lib, n), n
@@ -34,11 +35,12 @@ def test_status_strings():
 
 
 @pytest.mark.parametrize("batch,num_wg", [(1, 256), (16, 256), (32, 304), (3, 1), (1024, 64)])
-def test_workspace_size_is_one_slot_per_workgroup_and_sequence_plus_eight(batch, num_wg):
+def test_workspace_size_is_two_slots_per_workgroup_one_per_sequence_plus_eight(batch, num_wg):
     nbytes, used = mla.mla_decode_workspace_size(batch, 16, 65536, num_workgroups=num_wg)
     assert used == num_wg
     slot = 16 * 512 * 4 + 16 * 4
-    assert (num_wg + batch + 8) * slot <= nbytes <= (num_wg + batch + 8) * slot + 16
+    # a workgroup writes one partial result per query token it works for: at most two
+    assert (2 * num_wg + batch + 8) * slot <= nbytes <= (2 * num_wg + batch + 8) * slot + 16
     # independent of the KV length: the lengths live on the device
     assert mla.mla_decode_workspace_size(batch, 16, 7, num_workgroups=num_wg) == (nbytes, used)
 
@@ -59,6 +61,14 @@ def _call(q=0x1000, kv=0x2000, stride=4096 * 576, lens=0x3000, batch=2, heads=16
     vp = ctypes.c_void_p
     return mla.lib().mla_decode_ex(vp(q), vp(kv), stride, vp(lens), batch, heads, seqlen, scale, vp(out), vp(lse),
                                    vp(ws), ws_bytes, num_wg, phases, None)
+
+
+def test_planned_workgroups_argument_errors():
+    lib = mla.lib()
+    n = ctypes.c_int(0)
+    assert lib.mla_decode_planned_workgroups(1, None) == mla.MLA_ERR_INVALID_ARG
+    assert lib.mla_decode_planned_workgroups(0, ctypes.byref(n)) == mla.MLA_ERR_UNSUPPORTED_SHAPE
+    assert lib.mla_decode_planned_workgroups(9, ctypes.byref(n)) == mla.MLA_ERR_UNSUPPORTED_SHAPE
 
 
 def test_decode_argument_errors_come_before_any_device_work():

@@ -322,7 +322,7 @@ def _run_general(q, kv, lens, num_wg=None):
             lse.cpu().numpy().reshape(b * ql, 16).astype(np.float64))
 
 
-@pytest.mark.parametrize("q_len", [2, 3, 8])
+@pytest.mark.parametrize("q_len", [2, 3, 4, 5, 8])
 @pytest.mark.parametrize("num_wg", [None, 1, 5, 300])
 def test_several_query_tokens_small_ragged(oracle, q_len, num_wg):
     # lengths below q_len leave the first query tokens without any row (out 0, lse -inf)
@@ -334,15 +334,17 @@ def test_several_query_tokens_small_ragged(oracle, q_len, num_wg):
     _check(out, lse, ref_o.reshape(-1, 16, inputs.D_V), ref_l.reshape(-1, 16), label="q_len=%d num_wg=%s" % (q_len, num_wg))
 
 
-def test_two_query_tokens_many_sequences(oracle):
+@pytest.mark.parametrize("q_len", [2, 4])
+def test_several_query_tokens_many_sequences(oracle, q_len):
+    # pieces that cross sequence boundaries, with one workgroup per team (2 tokens) and with teams of two (4)
     g = torch.Generator().manual_seed(4321)
     lens = torch.randint(0, 300, (70,), generator=g).tolist()
-    q, kv, l = inputs.make_inputs(70, 300, lens, seed=412, poison_tail=True, q_len=2)
+    q, kv, l = inputs.make_inputs(70, 300, lens, seed=412, poison_tail=True, q_len=q_len)
     ref_o, ref_l = _oracle_general(oracle, q, kv, l, torch.bfloat16)
     for nwg in (None, 9):
-        print("case q_len 2 many sequences num_wg", nwg, flush=True)
+        print("case q_len", q_len, "many sequences num_wg", nwg, flush=True)
         out, lse = _run_general(q, kv, l, num_wg=nwg)
-        _check(out, lse, ref_o.reshape(-1, 16, inputs.D_V), ref_l.reshape(-1, 16), label="q_len=2 many num_wg=%s" % nwg)
+        _check(out, lse, ref_o.reshape(-1, 16, inputs.D_V), ref_l.reshape(-1, 16), label="q_len=%d many num_wg=%s" % (q_len, nwg))
 
 
 def test_two_query_tokens_fp16(oracle):
