@@ -298,24 +298,28 @@ __global__ void __launch_bounds__(kThreads, 1) mla_decode_split_kernel(const Par
             return my + lane * 16 + (lane >= boundary ? 16 : 0);
         }
     };
-    // Transposed orientation: MFMA row r of a score block is not token r of the tile's 16 but token
-    // rho(r) = 2 r mod 16 + (r >= 8), i.e. rows 0..7 are the even tokens and rows 8..15 the odd ones.
-    // The order of the tokens inside a tile is free (both products sum over them); this one lets
-    // the transposing V^T reads below, whose first 32 lanes touch the tokens of MFMA rows 0..7,
-    // fall on eight LDS rows whose bank ranges (row stride 292 words: 72 words apart for every
-    // second row) tile the 64 banks exactly.  With the identity order the eighth row wraps onto
-    // the first row's banks and every such read takes two passes.
-    const int k_row = kDirect ? r16 : ((2 * r16) & 15) + (r16 >> 3);
+    // MFMA position r (0..15) of a score block is not token r of the block's 16 tokens but a permuted
+    // one.  The order of the tokens inside a tile is free (both products sum over them); the one
+    // chosen lets each transposing V / V^T read below, whose first 32 lanes touch eight LDS rows, fall
+    // on rows of one parity: the row stride is 292 words, so every second row starts 72 = 64 + 8
+    // banks on and eight such rows of 8 words tile the 64 banks exactly.  With the identity order
+    // rows overlap in their banks and every such read takes two passes or more.
+    //   transposed: position r holds token rho(r) = 2 r mod 16 + (r >= 8): positions 0..7 (the rows
+    //               of k-groups 0 and 1) are the even tokens, 8..15 the odd ones
+    //   direct:     position t holds token tau(t) = 2 (t mod 4) + 8 (t / 8) + (t / 4 mod 2): the first
+    //               halves 8g .. 8g+3 of the k-groups are even tokens, the second halves the odd ones
+    const int k_row = kDirect ? 2 * (r16 & 3) + (r16 & 8) + ((r16 >> 2) & 1) : ((2 * r16) & 15) + (r16 >> 3);
     const int k_off = k_row * kLdsRow + g * 16;           // K operand: token k_row (+16), chunk 4*kk + g
     // V^T operand through the transposing read: within each 16-lane group, lane j points at
     // row j/4, columns 4*(j%4)..+3 of a 4x16 block and receives column j, rows 0..3.
     // Tokens of the two reads, in the order of the other operand's 8 k-values: transposed
-    // orientation rho(4g) .. rho(4g+3) and 16 more; direct orientation 8g..8g+3 and 8g+4..
+    // orientation rho(4g) .. rho(4g+3) and 16 more; direct orientation tau(8g) .. tau(8g+3) (in the
+    // second half of the tile for g >= 2) and the next row each, tau(t + 4) = tau(t) + 1
     // token of score-block row 4g + i (this lane's elements i = 0..3): rho(4g + i) = tok0 + 2 i
     const int tok0 = 8 * (g & 1) + (g >> 1);
-    const int v_row = kDirect ? 8 * g + (r16 >> 2) : tok0 + 2 * (r16 >> 2);
+    const int v_row = kDirect ? 16 * (g >> 1) + 8 * (g & 1) + 2 * (r16 >> 2) : tok0 + 2 * (r16 >> 2);
     const int v_off = v_row * kLdsRow + (r16 & 3) * 8;
-    constexpr int kVSecond = (kDirect ? 4 : 16) * kLdsRow;
+    constexpr int kVSecond = (kDirect ? 1 : 16) * kLdsRow;
     // direct orientation: P crosses lanes as fp32 [16 heads][32 tokens], in the rescale path's slot
     float *p_tr = reinterpret_cast<float *>(smem + kRescaleOff + w * 2048);
     float *stat_m = reinterpret_cast<float *>(smem + kStatsOff);
@@ -462,8 +466,8 @@ __global__ void __launch_bounds__(kThreads, 1) mla_decode_split_kernel(const Par
             }
             float pr[8];
             if constexpr (kDirect) {
-                // this lane holds, for token tb + r16 (s0) and tb + 16 + r16 (s1), heads 4g + i
-                const bool v0 = tb + r16 < t_end, v1 = tb + 16 + r16 < t_end;
+                // this lane holds, for token tb + k_row (s0) and tb + 16 + k_row (s1), heads 4g + i
+                const bool v0 = tb + k_row < t_end, v1 = tb + 16 + k_row < t_end;
                 f32x4 x0, x1, mx4;
 #pragma unroll
                 for (int i = 0; i < 4; ++i) {
