@@ -367,6 +367,39 @@ def test_two_query_tokens_headline_shape(oracle):
     _check(out, lse, ref_o.reshape(-1, 16, inputs.D_V), ref_l.reshape(-1, 16), label="q_len=2 headline")
 
 
+def test_seeded_random_small_cases(oracle):
+    """Forty seeded draws of (batch, lengths, q_len, element type, number of workgroups): the piece
+    boundaries, tile tails and causal limits fall differently in each, at sizes the oracle finishes at once."""
+    rng = np.random.default_rng(20250601)
+    for case in range(40):
+        batch = int(rng.integers(1, 10))
+        q_len = int(rng.choice([1, 1, 2, 2, 3, 4]))
+        max_len = int(rng.choice([40, 130, 300, 900]))
+        lens = [int(x) for x in rng.integers(0, max_len + 1, size=batch)]
+        if case % 5 == 0:
+            lens[int(rng.integers(0, batch))] = max_len          # one sequence fills its allocation
+        num_wg = int(rng.integers(1, 41)) if case % 3 else None
+        dtype = torch.float16 if case % 4 == 3 else torch.bfloat16
+        q, kv, l = inputs.make_inputs(batch, max_len, lens, seed=7000 + case, poison_tail=True, q_len=q_len, dtype=dtype)
+        ref_o, ref_l = _oracle_general(oracle, q, kv, l, dtype)
+        label = "random case %d: batch %d q_len %d lens %s num_wg %s %s" % (case, batch, q_len, lens, num_wg, str(dtype)[6:])
+        print(label, flush=True)
+        out, lse = _run_general(q, kv, l, num_wg=num_wg)
+        if dtype == torch.float16:
+            # One fp16 rounding of each probability: relative error 2^-12 / sqrt(3) rms per term, so an
+            # output element is off by that times sqrt(sum_t w_t^2 v_t^2) rms: up to 1.4e-4 |v| when one
+            # or two rows carry all the weight, as in these short sequences (|v| is about 1 here).
+            o, rl = ref_o.reshape(-1, 16, inputs.D_V), ref_l.reshape(-1, 16)
+            assert np.isfinite(out).all(), label
+            err = np.abs(out - o)
+            fin = np.isfinite(rl)
+            assert np.isneginf(lse[~fin]).all(), label
+            assert err.max() <= F16_MAX_ABS and math.sqrt(float((err ** 2).mean())) <= 1.5e-4, label
+            assert not fin.any() or np.abs(lse[fin] - rl[fin]).max() <= F16_LSE, label
+        else:
+            _check(out, lse, ref_o.reshape(-1, 16, inputs.D_V), ref_l.reshape(-1, 16), label=label)
+
+
 # ---- the original (non-transposed) orientation of Section 3.1, kept for the comparison of the two ----
 
 DIRECT = mla.PHASE_SPLIT | mla.PHASE_COMBINE | mla.ORIENT_DIRECT
