@@ -98,12 +98,12 @@ struct Params {
     const int *seqlens;       // [batch]
     float *out;               // [batch][16][512]
     float *lse;               // [batch][16]
-    float *part_out;          // [num_wg + batch][16][512]: slot of (workgroup k, sequence b) is k + b
-    float *part_lse;          // [num_wg + batch][16], base-2 log-sum-exp of scale*log2(e)*q.k
+    float *part_out;          // [(num_wg + batch) * q_len][16][512]: slot of (team k, sequence b, token j) is (k + b) q_len + j
+    float *part_lse;          // [(num_wg + batch) * q_len][16], base-2 log-sum-exp of scale*log2(e)*q.k
     int batch;                // sequences
     int q_len;                // query tokens per sequence
     int max_seqlen;
-    int num_wg;               // G: teams of q_len workgroups the unit stream is divided over (grid = G * q_len)
+    int num_wg;               // G: teams (one workgroup per two query tokens) the unit stream is divided over
     float scale_log2e;        // scale * log2(e): scores are kept in the base-2 domain
 };
 
