@@ -53,6 +53,7 @@
 #include <cmath>
 #include <cstdint>
 #include <mutex>
+#include <type_traits>
 
 #include "mla_decode.h"
 
@@ -80,6 +81,7 @@ static_assert(kUnit == MLA_UNIT_TOKENS, "header and kernel disagree on the sched
 constexpr int kCombineThreads = 128;
 constexpr int kSchedMfma = 0x008;              // instruction classes of sched_group_barrier
 constexpr int kSchedDsRead = 0x100;
+constexpr int kSchedVmemRead = 0x020;
 constexpr int kKAhead = 4;                     // k-steps of K operand reads in flight ahead of the QK MFMAs
 constexpr int kVAhead = 6;                     // value tiles of V^T reads in flight ahead of the PV MFMAs
 
@@ -426,9 +428,34 @@ __global__ void __launch_bounds__(kThreads, 1) mla_decode_split_kernel(const Par
             }
         };
 
+        // Two query tokens: the tile is written to LDS without refilling the registers; the loads of
+        // the next tile are issued one by one between the MFMAs of the two tiles worked on (below), the
+        // first 18 with the first tile, the other 18 with the second.  A compute unit takes in about
+        // 58 GB/s at most, whatever is in flight, and a wavefront waits at a load instruction until
+        // the memory path has room for it: a burst of 36 loads per wavefront costs 2.5 us during
+        // which nothing else is issued, while one load per 100 ns of matrix-core work costs nothing.
+        auto write_tile = [&]() {
+            int lane = l;
+            asm volatile("" : "+v"(lane));    // keeps the addresses from being hoisted out of the loop
+#pragma unroll
+            for (int i = 0; i < kTileLoads; ++i)
+                *reinterpret_cast<u32x4 *>(wr_addr(i, lane) + i * 1024 + ((i * 64) / 72) * 16) = st[i];
+        };
+        const char *rf_base = nullptr;    // next tile to fetch while tiles are worked on
+        int rf_last = 0;                  // byte offset of its last valid 16-byte chunk
+        auto refill_piece = [&](int i) {
+            const int piece = min(i * 1024, rf_last);                       // scalar
+            st[i] = load_stream16<kTeam>(rf_base + piece, min(lane16, (unsigned)(rf_last - piece)));
+        };
+        constexpr int kHalfLoads = kTileLoads / 2;     // 18 = 9 with the k-steps + 9 with the value tiles
+
         // ---- a3 to a6 on the 32 rows from row tb of the sequence that sit in an LDS tile (rd_k, rd_v:
-        // this lane's read addresses in that tile), for this wavefront's query token
-        auto process_tile = [&](const char *rd_k, const char *rd_v, const int tb) {
+        // this lane's read addresses in that tile), for this wavefront's query token; refill = 1 or 2
+        // spreads the first or second half of the next tile's loads over every other k-step and
+        // every other of the first 18 value tiles
+        auto process_tile = [&](auto refill, const char *rd_k, const char *rd_v, const int tb) {
+            constexpr int kRefill = decltype(refill)::value;
+            constexpr int kRefillBase = kRefill == 2 ? kHalfLoads : 0;
             // ---- a3: S^T = K Q^T for tokens 0..15 and 16..31 of the tile (equation (1)) --
             // LDS reads run kKAhead k-steps ahead of the MFMAs that consume them.
             f32x4 s0 = {0.f, 0.f, 0.f, 0.f}, s1 = {0.f, 0.f, 0.f, 0.f};
@@ -454,6 +481,9 @@ __global__ void __launch_bounds__(kThreads, 1) mla_decode_split_kernel(const Par
                         s0 = mfma_16x16x32<kDtype>(k0, qf[kk], s0);
                         s1 = mfma_16x16x32<kDtype>(k1, qf[kk], s1);
                     }
+                    if constexpr (kRefill != 0) {
+                        if (kk % 2 == 0) refill_piece(kRefillBase + kk / 2);
+                    }
                 }
                 // pin that interleaving for the instruction scheduler: reads first, then
                 // (2 MFMA, 2 LDS reads) per k-step, so LDS latency hides behind the MFMAs
@@ -462,6 +492,9 @@ __global__ void __launch_bounds__(kThreads, 1) mla_decode_split_kernel(const Par
                 for (int kk = 0; kk < kKSteps; ++kk) {
                     __builtin_amdgcn_sched_group_barrier(kSchedMfma, 2, 0);
                     if (kk + kKAhead < kKSteps) __builtin_amdgcn_sched_group_barrier(kSchedDsRead, 2, 0);
+                    if constexpr (kRefill != 0) {
+                        if (kk % 2 == 0) __builtin_amdgcn_sched_group_barrier(kSchedVmemRead, 1, 0);
+                    }
                 }
             }
             float pr[8];
@@ -599,12 +632,18 @@ __global__ void __launch_bounds__(kThreads, 1) mla_decode_split_kernel(const Par
                         o[ct] = mfma_16x16x32<kDtype>(vt, p_hi, o[ct]);
                         if constexpr (kPTerms == 2) o[ct] = mfma_16x16x32<kDtype>(vt, p_lo, o[ct]);
                     }
+                    if constexpr (kRefill != 0) {
+                        if (ct % 2 == 0 && ct / 2 < kHalfLoads - kKSteps / 2) refill_piece(kRefillBase + kKSteps / 2 + ct / 2);
+                    }
                 }
                 __builtin_amdgcn_sched_group_barrier(kSchedDsRead, 2 * kVAhead, 1);
 #pragma unroll
                 for (int ct = 0; ct < kDvTiles; ++ct) {
                     __builtin_amdgcn_sched_group_barrier(kSchedMfma, kPTerms, 1);
                     if (ct + kVAhead < kDvTiles) __builtin_amdgcn_sched_group_barrier(kSchedDsRead, 2, 1);
+                    if constexpr (kRefill != 0) {
+                        if (ct % 2 == 0 && ct / 2 < kHalfLoads - kKSteps / 2) __builtin_amdgcn_sched_group_barrier(kSchedVmemRead, 1, 1);
+                    }
                 }
             }
         };
@@ -612,7 +651,7 @@ __global__ void __launch_bounds__(kThreads, 1) mla_decode_split_kernel(const Par
         if constexpr (kShare == 1) {
             while (cur < n_tiles) {
                 stage_tile();
-                process_tile(my + k_off, my + v_off, t_begin + cur * kTile);
+                process_tile(std::integral_constant<int, 0>{}, my + k_off, my + v_off, t_begin + cur * kTile);
                 cur = nxt;
                 nxt += kWaves;
             }
@@ -623,15 +662,33 @@ __global__ void __launch_bounds__(kThreads, 1) mla_decode_split_kernel(const Par
             // in flight.  The barriers are reached by all wavefronts the same number of times
             // (n_tiles is the same for all of them).
             for (int base = 0; base < n_tiles; base += kWaves) {
-                if (cur < n_tiles) stage_tile();
+                // While the two tiles are worked on, the registers are refilled with this wavefront's next
+                // tile (after its last tile: with 36 reads of the sequence's first KB, which cost next to
+                // nothing and keep the code free of further variants).
+                const bool fetch = nxt < n_tiles;
+                const int ntb = fetch ? t_begin + nxt * kTile : 0;
+                rf_last = fetch ? (min(n - ntb, kTile) * (kRowBytes / 16) - 1) * 16 : 1008;
+                rf_base = kv_b + (long long)ntb * kRowBytes;
+                if (cur < n_tiles) write_tile();
+                {
+                    const int tb = t_begin + cur * kTile;
+                    if (cur < n_tiles && tb < t_end) {               // own tile: staged, and visible to this token
+                        process_tile(std::integral_constant<int, 1>{}, my + k_off, my + v_off, tb);
+                    } else {
 #pragma unroll
-                for (int sh = 0; sh < kShare; ++sh) {
-                    if (sh == 1) __syncthreads();                    // the neighbours' tiles are in LDS
-                    const int ws = (w & ~(kShare - 1)) | ((tk + sh) & (kShare - 1));
+                        for (int i = 0; i < kHalfLoads; ++i) refill_piece(i);
+                    }
+                }
+                __syncthreads();                                     // the neighbour's tile is in LDS
+                {
+                    const int ws = w ^ 1;
                     const int tb = t_begin + (base + ws) * kTile;
                     if (base + ws < n_tiles && tb < t_end) {         // staged, and visible to this token
                         const char *tile = smem + ws * kWaveLds;
-                        process_tile(tile + k_off, tile + v_off, tb);
+                        process_tile(std::integral_constant<int, 2>{}, tile + k_off, tile + v_off, tb);
+                    } else {
+#pragma unroll
+                        for (int i = kHalfLoads; i < kTileLoads; ++i) refill_piece(i);
                     }
                 }
                 __syncthreads();                                     // before the tiles are overwritten
