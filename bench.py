@@ -131,7 +131,7 @@ def main():
         kvs.append(kvs[0].clone())
     nwg = args.workgroups or None
     need, _ = mla.mla_decode_workspace_size(batch * args.q_len, 16, max_seqlen, args.workgroups)
-    nwg_used = args.workgroups or mla.mla_decode_planned_workgroups(args.q_len)
+    nwg_used = args.workgroups or mla.mla_decode_planned_workgroups(batch, args.q_len, max_seqlen)
     ws = torch.empty((need,), dtype=torch.uint8, device=dev)
     out = torch.empty((batch, args.q_len, 16, 512), dtype=torch.float32, device=dev)
     lse = torch.empty((batch, args.q_len, 16), dtype=torch.float32, device=dev)

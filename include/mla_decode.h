@@ -52,8 +52,9 @@ typedef enum {
 /*
  * Workspace size.  Host only, deterministic, touches no device unless
  * num_workgroups == 0 (then the compute-unit count of the current HIP device is
- * queried: the automatic plan is a persistent workgroup on 11 of every 16 compute
- * units, which is where HBM saturates).
+ * queried: the automatic plan is a persistent workgroup on 13 of every 16 compute
+ * units, or on every one when the KV stream is short, see
+ * mla_decode_planned_workgroups()).
  * The size depends only on (batch, number of workgroups), never on the
  * per-sequence lengths, which live on the device: one partial result (16 x 512 fp32 plus
  * 16 log-sum-exps) for 2 * num_workgroups + batch + MLA_MAX_Q_LEN slots; a workgroup
@@ -165,11 +166,14 @@ mla_status_t mla_decode_typed(const void *q, const void *kv_cache, int64_t kv_ba
 
 /*
  * The number of workgroups the automatic plan (num_workgroups == 0) launches on the current HIP
- * device for q_len query tokens per sequence: 11 of every 16 compute units for one token, every
- * compute unit for more.  Host only.  q_len outside 1 .. MLA_MAX_Q_LEN is
- * MLA_ERR_UNSUPPORTED_SHAPE, a NULL pointer MLA_ERR_INVALID_ARG.
+ * device for `batch` sequences of at most max_seqlen_kv rows and q_len query tokens each: 13 of
+ * every 16 compute units for one token and a long KV stream (batch * ceil(max_seqlen_kv / 128)
+ * above 8 per compute unit), every compute unit otherwise.  Host only.  q_len outside
+ * 1 .. MLA_MAX_Q_LEN is MLA_ERR_UNSUPPORTED_SHAPE; a NULL pointer, batch < 1 or
+ * max_seqlen_kv < 1 MLA_ERR_INVALID_ARG.
  */
-mla_status_t mla_decode_planned_workgroups(int q_len, int *num_workgroups);
+mla_status_t mla_decode_planned_workgroups(int batch, int q_len, int max_seqlen_kv,
+                                           int *num_workgroups);
 
 /* Static string for a status code (never NULL). */
 const char *mla_status_string(mla_status_t status);

@@ -287,19 +287,6 @@ __global__ void __launch_bounds__(kThreads, 1) mla_decode_split_kernel(const Par
         const int boundary = 72 * ((r * 64) / 72 + 1) - r * 64;     // 72, 8, 16, ..., 56, 64
         wr_flat[r] = my + l * 16 + (l >= boundary ? 16 : 0);
     }
-    // With two query tokens a few more values are live across the tile loop and the nine addresses
-    // would push others out of the register file (a value reloaded from scratch memory inside the
-    // loop has to wait for every KV load issued before it).  There the address is worked out at
-    // each write from the lane number, which costs two vector instructions per 1 KB written.
-    auto wr_addr = [&](int i, int lane) -> char * {
-        if constexpr (kShare == 1) {
-            return wr_flat[i % 9];
-        } else {
-            const int r = i % 9;
-            const int boundary = 72 * ((r * 64) / 72 + 1) - r * 64;
-            return my + lane * 16 + (lane >= boundary ? 16 : 0);
-        }
-    };
     // MFMA position r (0..15) of a score block is not token r of the block's 16 tokens but a permuted
     // one.  The order of the tokens inside a tile is free (both products sum over them); the one
     // chosen lets each transposing V / V^T read below, whose first 32 lanes touch eight LDS rows, fall
@@ -398,48 +385,16 @@ __global__ void __launch_bounds__(kThreads, 1) mla_decode_split_kernel(const Par
         bool first_tile = true;
 
         // ---- a2: registers -> private LDS tile --------------------------------------------
-        auto stage_tile = [&]() {
-            int lane = l;
-            if constexpr (kShare > 1) asm volatile("" : "+v"(lane));   // keeps the addresses from being hoisted out of the loop
-            // chunk c = 64 i + l goes to row c / 72, column chunk c % 72: byte 16 (c + c / 72)
-            // Each piece's register is refilled with the same piece of the next tile as soon as it
-            // has been written to LDS, so this wavefront keeps 35 requests in flight at all times
-            // instead of draining to none before it asks again.
-            if (nxt < n_tiles) {
-                const int ntb = t_begin + nxt * kTile;
-                const int valid_rows = min(n - ntb, kTile);                 // >= 1
-                const int last_chunk16 = (valid_rows * (kRowBytes / 16) - 1) * 16;
-                const char *tile_base = kv_b + (long long)ntb * kRowBytes;
-#pragma unroll
-                for (int i = 0; i < kTileLoads; ++i) {
-                    *reinterpret_cast<u32x4 *>(wr_addr(i, lane) + i * 1024 + ((i * 64) / 72) * 16) = st[i];
-                    const int piece = min(i * 1024, last_chunk16);          // scalar
-                    st[i] = load_stream16<kTeam>(tile_base + piece, min(lane16, (unsigned)(last_chunk16 - piece)));
-                }
-#pragma unroll
-                for (int i = 0; i < kTileLoads; ++i) {
-                    __builtin_amdgcn_sched_group_barrier(0x200, 1, 2);      // one LDS write
-                    __builtin_amdgcn_sched_group_barrier(0x020, 1, 2);      // one global load
-                }
-            } else {
-#pragma unroll
-                for (int i = 0; i < kTileLoads; ++i)
-                    *reinterpret_cast<u32x4 *>(wr_addr(i, lane) + i * 1024 + ((i * 64) / 72) * 16) = st[i];
-            }
-        };
-
-        // Two query tokens: the tile is written to LDS without refilling the registers; the loads of
-        // the next tile are issued one by one between the MFMAs of the two tiles worked on (below), the
-        // first 18 with the first tile, the other 18 with the second.  A compute unit takes in about
+        // chunk c = 64 i + l goes to row c / 72, column chunk c % 72: byte 16 (c + c / 72).
+        // The registers are not refilled here: the loads of the next tile are issued one by one
+        // between the MFMAs of the tile(s) worked on next (below).  A compute unit takes in about
         // 58 GB/s at most, whatever is in flight, and a wavefront waits at a load instruction until
-        // the memory path has room for it: a burst of 36 loads per wavefront costs 2.5 us during
-        // which nothing else is issued, while one load per 100 ns of matrix-core work costs nothing.
+        // the memory path has room for it: a burst of 36 loads per wavefront costs up to 2.5 us during
+        // which it issues nothing else, while one load per 30-100 ns of matrix-core work costs nothing.
         auto write_tile = [&]() {
-            int lane = l;
-            asm volatile("" : "+v"(lane));    // keeps the addresses from being hoisted out of the loop
 #pragma unroll
             for (int i = 0; i < kTileLoads; ++i)
-                *reinterpret_cast<u32x4 *>(wr_addr(i, lane) + i * 1024 + ((i * 64) / 72) * 16) = st[i];
+                *reinterpret_cast<u32x4 *>(wr_flat[i % 9] + i * 1024 + ((i * 64) / 72) * 16) = st[i];
         };
         const char *rf_base = nullptr;    // next tile to fetch while tiles are worked on
         int rf_last = 0;                  // byte offset of its last valid 16-byte chunk
@@ -447,12 +402,21 @@ __global__ void __launch_bounds__(kThreads, 1) mla_decode_split_kernel(const Par
             const int piece = min(i * 1024, rf_last);                       // scalar
             st[i] = load_stream16<kTeam>(rf_base + piece, min(lane16, (unsigned)(rf_last - piece)));
         };
+        // The tile to fetch next: this wavefront's next tile of the piece; after its last tile, 36 reads
+        // of the sequence's first KB, which cost next to nothing and keep the loop free of a second variant.
+        auto set_refill = [&]() {
+            const bool fetch = nxt < n_tiles;
+            const int ntb = fetch ? t_begin + nxt * kTile : 0;
+            rf_last = fetch ? (min(n - ntb, kTile) * (kRowBytes / 16) - 1) * 16 : 1008;
+            rf_base = kv_b + (long long)ntb * kRowBytes;
+        };
         constexpr int kHalfLoads = kTileLoads / 2;     // 18 = 9 with the k-steps + 9 with the value tiles
 
         // ---- a3 to a6 on the 32 rows from row tb of the sequence that sit in an LDS tile (rd_k, rd_v:
-        // this lane's read addresses in that tile), for this wavefront's query token; refill = 1 or 2
-        // spreads the first or second half of the next tile's loads over every other k-step and
-        // every other of the first 18 value tiles
+        // this lane's read addresses in that tile), for this wavefront's query token.  refill says
+        // which loads of the next tile go between the MFMAs: 0 none; 3 all 36, one per k-step and one
+        // per value tile for the first 18 (one query token: one tile per round); 1 or 2 the first or
+        // second 18, one per other k-step and other value tile (two tokens: two tiles per round)
         auto process_tile = [&](auto refill, const char *rd_k, const char *rd_v, const int tb) {
             constexpr int kRefill = decltype(refill)::value;
             constexpr int kRefillBase = kRefill == 2 ? kHalfLoads : 0;
@@ -481,7 +445,9 @@ __global__ void __launch_bounds__(kThreads, 1) mla_decode_split_kernel(const Par
                         s0 = mfma_16x16x32<kDtype>(k0, qf[kk], s0);
                         s1 = mfma_16x16x32<kDtype>(k1, qf[kk], s1);
                     }
-                    if constexpr (kRefill != 0) {
+                    if constexpr (kRefill == 3) {
+                        refill_piece(kk);
+                    } else if constexpr (kRefill != 0) {
                         if (kk % 2 == 0) refill_piece(kRefillBase + kk / 2);
                     }
                 }
@@ -492,7 +458,9 @@ __global__ void __launch_bounds__(kThreads, 1) mla_decode_split_kernel(const Par
                 for (int kk = 0; kk < kKSteps; ++kk) {
                     __builtin_amdgcn_sched_group_barrier(kSchedMfma, 2, 0);
                     if (kk + kKAhead < kKSteps) __builtin_amdgcn_sched_group_barrier(kSchedDsRead, 2, 0);
-                    if constexpr (kRefill != 0) {
+                    if constexpr (kRefill == 3) {
+                        __builtin_amdgcn_sched_group_barrier(kSchedVmemRead, 1, 0);
+                    } else if constexpr (kRefill != 0) {
                         if (kk % 2 == 0) __builtin_amdgcn_sched_group_barrier(kSchedVmemRead, 1, 0);
                     }
                 }
@@ -632,7 +600,9 @@ __global__ void __launch_bounds__(kThreads, 1) mla_decode_split_kernel(const Par
                         o[ct] = mfma_16x16x32<kDtype>(vt, p_hi, o[ct]);
                         if constexpr (kPTerms == 2) o[ct] = mfma_16x16x32<kDtype>(vt, p_lo, o[ct]);
                     }
-                    if constexpr (kRefill != 0) {
+                    if constexpr (kRefill == 3) {
+                        if (ct < kTileLoads - kKSteps) refill_piece(kKSteps + ct);
+                    } else if constexpr (kRefill != 0) {
                         if (ct % 2 == 0 && ct / 2 < kHalfLoads - kKSteps / 2) refill_piece(kRefillBase + kKSteps / 2 + ct / 2);
                     }
                 }
@@ -641,7 +611,9 @@ __global__ void __launch_bounds__(kThreads, 1) mla_decode_split_kernel(const Par
                 for (int ct = 0; ct < kDvTiles; ++ct) {
                     __builtin_amdgcn_sched_group_barrier(kSchedMfma, kPTerms, 1);
                     if (ct + kVAhead < kDvTiles) __builtin_amdgcn_sched_group_barrier(kSchedDsRead, 2, 1);
-                    if constexpr (kRefill != 0) {
+                    if constexpr (kRefill == 3) {
+                        if (ct < kTileLoads - kKSteps) __builtin_amdgcn_sched_group_barrier(kSchedVmemRead, 1, 1);
+                    } else if constexpr (kRefill != 0) {
                         if (ct % 2 == 0 && ct / 2 < kHalfLoads - kKSteps / 2) __builtin_amdgcn_sched_group_barrier(kSchedVmemRead, 1, 1);
                     }
                 }
@@ -650,8 +622,9 @@ __global__ void __launch_bounds__(kThreads, 1) mla_decode_split_kernel(const Par
 
         if constexpr (kShare == 1) {
             while (cur < n_tiles) {
-                stage_tile();
-                process_tile(std::integral_constant<int, 0>{}, my + k_off, my + v_off, t_begin + cur * kTile);
+                set_refill();
+                write_tile();
+                process_tile(std::integral_constant<int, 3>{}, my + k_off, my + v_off, t_begin + cur * kTile);
                 cur = nxt;
                 nxt += kWaves;
             }
@@ -662,13 +635,8 @@ __global__ void __launch_bounds__(kThreads, 1) mla_decode_split_kernel(const Par
             // in flight.  The barriers are reached by all wavefronts the same number of times
             // (n_tiles is the same for all of them).
             for (int base = 0; base < n_tiles; base += kWaves) {
-                // While the two tiles are worked on, the registers are refilled with this wavefront's next
-                // tile (after its last tile: with 36 reads of the sequence's first KB, which cost next to
-                // nothing and keep the code free of further variants).
-                const bool fetch = nxt < n_tiles;
-                const int ntb = fetch ? t_begin + nxt * kTile : 0;
-                rf_last = fetch ? (min(n - ntb, kTile) * (kRowBytes / 16) - 1) * 16 : 1008;
-                rf_base = kv_b + (long long)ntb * kRowBytes;
+                // While the two tiles are worked on, the registers are refilled with this wavefront's next tile.
+                set_refill();
                 if (cur < n_tiles) write_tile();
                 {
                     const int tb = t_begin + cur * kTile;
@@ -1000,19 +968,23 @@ mla_status_t launch(const void *q, const void *kv_cache, int64_t kv_batch_stride
 
 extern "C" {
 
-// Automatic plan: persistent workgroups for 11/16 of the compute units.  One workgroup fills a
-// compute unit (LDS), and HBM is saturated well before every unit streams: on 256 units the
-// kernel is fastest with 160-192 workgroups; beyond that the extra requests only add contention
-// and pairs of XCDs stop sharing their path to memory evenly, so the slowest workgroup gets later.
-// With several query tokens per sequence every KV row is worked on q_len times, the path is
-// no longer purely bandwidth-bound, and all compute units are used (measured at batch 16, KV 64K,
-// two tokens: 243 us on 256 workgroups, 291 us on 176).
-static mla_status_t planned_workgroups(int q_len, int *num_wg, int *num_wg_max) {
+// Automatic plan.  One workgroup fills a compute unit (LDS), and a compute unit takes in about
+// 58 GB/s at most, so HBM is saturated by well under all of them.  With one query token and a long
+// KV stream (more than 8 units of 128 rows per compute unit) the plan is a persistent workgroup on
+// 13 of every 16 compute units: measured over the batch 16 / 32, KV 16K ... 64K grid and the
+// ragged batch, 176 ... 224 workgroups are within 1 % of each other and 208 is the best or second
+// best everywhere, while 256 is 1-2 % slower at the long end (the slowest workgroup gets later).
+// With a short stream every compute unit is used, so that each workgroup holds as few units as
+// possible (batch 32, KV 2K: 27.9 us on 256 workgroups, 33.1 us on 208).  With several query
+// tokens every KV row is worked on q_len times, the kernel is bound by what a compute unit can
+// do, and every compute unit is used (batch 16, KV 64K, two tokens: 190.7 us on 256, 199.3 us on 208).
+static mla_status_t planned_workgroups(int batch, int q_len, int max_seqlen_kv, int *num_wg, int *num_wg_max) {
     int dev = 0, cus = 0;
     if (hipGetDevice(&dev) != hipSuccess) return MLA_ERR_HIP;
     if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0)
         return MLA_ERR_HIP;
-    const int n = q_len > 1 ? cus : cus * 11 / 16;
+    const long long units_max = (long long)batch * ((max_seqlen_kv + kUnit - 1) / kUnit);
+    const int n = (q_len > 1 || units_max <= 8ll * cus) ? cus : cus * 13 / 16;
     *num_wg = n < 1 ? 1 : n;
     if (num_wg_max) *num_wg_max = cus;
     return MLA_OK;
@@ -1026,7 +998,7 @@ mla_status_t mla_decode_workspace_size(int batch, int num_heads, int max_seqlen_
     if (num_workgroups < 0 || num_workgroups > kMaxWorkgroups) return MLA_ERR_INVALID_ARG;
     int size_for = num_workgroups;
     if (num_workgroups == 0) {        // the size covers the plan for any number of query tokens
-        st = planned_workgroups(1, &num_workgroups, &size_for);
+        st = planned_workgroups(batch, 1, max_seqlen_kv, &num_workgroups, &size_for);
         if (st != MLA_OK) return st;
     }
     *bytes = workspace_bytes_for(batch, size_for);
@@ -1050,7 +1022,7 @@ mla_status_t mla_decode_typed(const void *q, const void *kv_cache, int64_t kv_ba
     if ((flags & ~(MLA_PHASE_SPLIT | MLA_PHASE_COMBINE | MLA_ORIENT_DIRECT)) != 0) return MLA_ERR_INVALID_ARG;
     if ((flags & (MLA_PHASE_SPLIT | MLA_PHASE_COMBINE)) == 0) return MLA_ERR_INVALID_ARG;
     if (num_workgroups == 0) {
-        st = planned_workgroups(q_len, &num_workgroups, nullptr);
+        st = planned_workgroups(batch, q_len, max_seqlen_kv, &num_workgroups, nullptr);
         if (st != MLA_OK) return st;
     }
     return launch(q, kv_cache, kv_batch_stride, cache_seqlens, batch, q_len, max_seqlen_kv, scale, out, lse,
@@ -1074,10 +1046,10 @@ mla_status_t mla_decode(const void *q, const void *kv_cache, int64_t kv_batch_st
                          out, lse, workspace, workspace_bytes, 0, MLA_PHASE_SPLIT | MLA_PHASE_COMBINE, stream);
 }
 
-mla_status_t mla_decode_planned_workgroups(int q_len, int *num_workgroups) {
-    if (!num_workgroups) return MLA_ERR_INVALID_ARG;
+mla_status_t mla_decode_planned_workgroups(int batch, int q_len, int max_seqlen_kv, int *num_workgroups) {
+    if (!num_workgroups || batch <= 0 || max_seqlen_kv <= 0) return MLA_ERR_INVALID_ARG;
     if (q_len < 1 || q_len > kMaxQLen) return MLA_ERR_UNSUPPORTED_SHAPE;
-    return planned_workgroups(q_len, num_workgroups, nullptr);
+    return planned_workgroups(batch, q_len, max_seqlen_kv, num_workgroups, nullptr);
 }
 
 const char *mla_status_string(mla_status_t status) {

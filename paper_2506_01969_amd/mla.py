@@ -54,7 +54,7 @@ def lib():
         L.mla_decode_typed.argtypes = [vp, vp, ctypes.c_int64, vp, ci, ci, ci, ci, ci, ctypes.c_float, vp, vp,
                                        vp, sz, ci, ci, vp]
         L.mla_decode_typed.restype = ci
-        L.mla_decode_planned_workgroups.argtypes = [ci, cip]
+        L.mla_decode_planned_workgroups.argtypes = [ci, ci, ci, cip]
         L.mla_decode_planned_workgroups.restype = ci
         L.mla_status_string.argtypes = [ci]
         L.mla_status_string.restype = ctypes.c_char_p
@@ -72,10 +72,10 @@ def mla_decode_workspace_size(batch, num_heads, max_seqlen_kv, num_workgroups=0)
     return nbytes.value, used.value
 
 
-def mla_decode_planned_workgroups(q_len=1):
-    """Workgroups the automatic plan launches on the current device for q_len query tokens."""
+def mla_decode_planned_workgroups(batch, q_len, max_seqlen_kv):
+    """Workgroups the automatic plan launches on the current device for this shape."""
     n = ctypes.c_int(0)
-    st = lib().mla_decode_planned_workgroups(q_len, ctypes.byref(n))
+    st = lib().mla_decode_planned_workgroups(batch, q_len, max_seqlen_kv, ctypes.byref(n))
     if st != MLA_OK:
         raise MlaError(st, "mla_decode_planned_workgroups")
     return n.value

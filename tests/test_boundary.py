@@ -66,9 +66,11 @@ def _call(q=0x1000, kv=0x2000, stride=4096 * 576, lens=0x3000, batch=2, heads=16
 def test_planned_workgroups_argument_errors():
     lib = mla.lib()
     n = ctypes.c_int(0)
-    assert lib.mla_decode_planned_workgroups(1, None) == mla.MLA_ERR_INVALID_ARG
-    assert lib.mla_decode_planned_workgroups(0, ctypes.byref(n)) == mla.MLA_ERR_UNSUPPORTED_SHAPE
-    assert lib.mla_decode_planned_workgroups(9, ctypes.byref(n)) == mla.MLA_ERR_UNSUPPORTED_SHAPE
+    assert lib.mla_decode_planned_workgroups(16, 1, 4096, None) == mla.MLA_ERR_INVALID_ARG
+    assert lib.mla_decode_planned_workgroups(0, 1, 4096, ctypes.byref(n)) == mla.MLA_ERR_INVALID_ARG
+    assert lib.mla_decode_planned_workgroups(16, 1, 0, ctypes.byref(n)) == mla.MLA_ERR_INVALID_ARG
+    assert lib.mla_decode_planned_workgroups(16, 0, 4096, ctypes.byref(n)) == mla.MLA_ERR_UNSUPPORTED_SHAPE
+    assert lib.mla_decode_planned_workgroups(16, 9, 4096, ctypes.byref(n)) == mla.MLA_ERR_UNSUPPORTED_SHAPE
 
 
 def test_decode_argument_errors_come_before_any_device_work():
