@@ -27,11 +27,12 @@
 //
 // Each wavefront is an independent online-softmax worker (the m / l / rescale recurrence of
 // Algorithm 1) over every 4th 32-token tile of the piece, with a private LDS tile, so the main
-// loop has no barrier.  A tile is fetched with 16-byte coalesced
-// global loads into registers (in flight while the previous tile is being computed; each register
-// is refilled with its piece of the next tile the moment it has been copied to LDS), written
-// once to LDS, and read twice from LDS: as the K operand (ds_read_b128) and, through the
-// transposing LDS read ds_read_b64_tr_b16, as the V^T operand.  The four wavefronts of a
+// loop has no barrier.  A tile is fetched with 16-byte coalesced global loads into registers (in
+// flight while the previous tile is being computed; the 36 loads of a tile are issued one by one
+// between the MFMAs of the tile before it, never in a burst: a wavefront waits at a load
+// instruction until the compute unit's memory path has room for it), written once to LDS, and
+// read twice from LDS: as the K operand (ds_read_b128) and, through the transposing LDS read
+// ds_read_b64_tr_b16, as the V^T operand.  The four wavefronts of a
 // workgroup merge their (m, l, O) through LDS at the end of the piece; a sequence shared by
 // several workgroups is finished by the combine kernel.
 //
