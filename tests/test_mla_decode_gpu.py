@@ -367,6 +367,38 @@ def test_two_query_tokens_headline_shape(oracle):
     _check(out, lse, ref_o.reshape(-1, 16, inputs.D_V), ref_l.reshape(-1, 16), label="q_len=2 headline")
 
 
+def test_two_query_tokens_repeat_is_bit_identical_and_workspace_contents_do_not_matter():
+    """The wavefront pairs read each other's LDS tiles between barriers; the result must not depend on
+    timing or on what the workspace held (0xFF.. is NaN as fp32)."""
+    dev = _dev()
+    q, kv, l = inputs.make_inputs(5, 3000, [3000, 2999, 2, 1500, 641], seed=131, poison_tail=True, q_len=2)
+    qd, kvd, ld = q.to(dev), kv.to(dev), l.to(dev)
+    need, _ = mla.mla_decode_workspace_size(5 * 2, 16, 3000, 0)
+    ws = torch.empty((need,), dtype=torch.uint8, device=dev)
+    outs = []
+    for fill in (0x00, 0xFF, 0x7F, 0x00):
+        ws.fill_(fill)
+        out = torch.full((5, 2, 16, 512), float("nan"), dtype=torch.float32, device=dev)
+        lse = torch.full((5, 2, 16), float("nan"), dtype=torch.float32, device=dev)
+        print("case q_len 2 repeat fill", fill, flush=True)
+        mla.mla_decode(qd, kvd, ld, inputs.SCALE, out=out, lse=lse, workspace=ws)
+        torch.cuda.synchronize()
+        outs.append((out.cpu(), lse.cpu()))
+    assert torch.isfinite(outs[0][0]).all()
+    for o, s in outs[1:]:
+        assert torch.equal(o, outs[0][0]) and torch.equal(s, outs[0][1])
+
+
+def test_automatic_plan_follows_the_shape():
+    _dev()
+    cus = torch.cuda.get_device_properties(0).multi_processor_count
+    long_kv = mla.mla_decode_planned_workgroups(16, 1, 65536)
+    assert long_kv == cus * 13 // 16
+    assert mla.mla_decode_planned_workgroups(16, 1, 4096) == cus          # 512 units: a short stream
+    assert mla.mla_decode_planned_workgroups(16, 2, 65536) == cus         # several query tokens
+    assert mla.mla_decode_workspace_size(16, 16, 65536, 0)[1] == long_kv
+
+
 def test_seeded_random_small_cases(oracle):
     """Forty seeded draws of (batch, lengths, q_len, element type, number of workgroups): the piece
     boundaries, tile tails and causal limits fall differently in each, at sizes the oracle finishes at once."""
