@@ -79,7 +79,8 @@ constexpr int kLdsBytes = kRescaleOff + kWaves * 2048;
 static_assert(kLdsBytes <= 160 * 1024, "LDS of one compute unit");
 constexpr int kUnit = kWaves * kTile;          // 128 tokens: the scheduling unit (one tile per wavefront)
 static_assert(kUnit == MLA_UNIT_TOKENS, "header and kernel disagree on the scheduling unit");
-constexpr int kCombineThreads = 128;
+constexpr int kCombineCols = 128;               // threads that cover the 512 value columns, 4 each
+constexpr int kCombineWide = 4;                 // groups of such threads per block when a sequence has many pieces
 constexpr int kSchedMfma = 0x008;              // instruction classes of sched_group_barrier
 constexpr int kSchedDsRead = 0x100;
 constexpr int kSchedVmemRead = 0x020;
@@ -774,19 +775,23 @@ __global__ void __launch_bounds__(kThreads, 1) mla_decode_split_kernel(const Par
 // Combine kernel (step a8): per (sequence, head), merge the partial results of the workgroups
 // that shared the sequence by log-sum-exp: the m / l recurrence of Algorithm 1 applied across
 // workgroups instead of KV blocks.  The set of workgroups follows from the same partition.
-__global__ void __launch_bounds__(kCombineThreads) mla_decode_combine_kernel(const Params p) {
+template <int kCombineGroups>
+__global__ void __launch_bounds__(kCombineCols * kCombineGroups) mla_decode_combine_kernel(const Params p) {
     const int row = blockIdx.x / kHeads;      // (sequence, query token)
     const int h = blockIdx.x - row * kHeads;
     const int b = row / p.q_len;
     const int j = row - b * p.q_len;
-    const int t = threadIdx.x;                // 128 threads x 4 columns
+    const int t = threadIdx.x & (kCombineCols - 1);   // 128 threads x 4 columns
+    const int pg = threadIdx.x / kCombineCols;        // group of pieces (wave-uniform)
     int total_units, seq_first;
     unit_sums(p, t & 63, b, total_units, seq_first);
     const int ub = units_of(clamped_len(p, b));
     float *out = p.out + ((long long)row * kHeads + h) * kDv + t * 4;
     if (ub == 0) {                            // empty sequence
-        *reinterpret_cast<f32x4 *>(out) = f32x4{0.f, 0.f, 0.f, 0.f};
-        if (t == 0) p.lse[row * kHeads + h] = -INFINITY;
+        if (pg == 0) {
+            *reinterpret_cast<f32x4 *>(out) = f32x4{0.f, 0.f, 0.f, 0.f};
+            if (t == 0) p.lse[row * kHeads + h] = -INFINITY;
+        }
         return;
     }
     const int active = total_units < p.num_wg ? total_units : p.num_wg;    // as in the main kernel
@@ -800,20 +805,24 @@ __global__ void __launch_bounds__(kCombineThreads) mla_decode_combine_kernel(con
     const long long ostep = (long long)p.q_len * kHeads * kDv;
     const float *pl = p.part_lse + first_slot * kHeads + h;
     const float *po = p.part_out + (first_slot * kHeads + h) * kDv + t * 4;
-    // The kernel is a chain of memory round trips, so every load of up to kBatch pieces (their
-    // log-sum-exps and this thread's four columns) is issued before anything is waited for; more
-    // pieces than that are folded in batch by batch with the same running-maximum recurrence.
+    // The kernel is a chain of memory round trips, so the pieces are dealt to the block's thread
+    // groups in turn (one group, or four when the host expects more than kBatch pieces per sequence:
+    // few sequences over many workgroups), and each group issues every load of up to kBatch of its pieces (their
+    // log-sum-exps and the thread's four columns) before anything is waited for; more pieces than
+    // that are folded in batch by batch with the same running-maximum recurrence.  The groups'
+    // results are merged through LDS at the end.
     constexpr int kBatch = 16;
     float m = -INFINITY, sum = 0.f;
     f32x4 acc = {0.f, 0.f, 0.f, 0.f};
-    for (int s0 = 0; s0 < ns; s0 += kBatch) {
+    for (int s0 = pg; s0 < ns; s0 += kBatch * kCombineGroups) {
         float ls[kBatch];
         f32x4 v[kBatch];
 #pragma unroll
         for (int i = 0; i < kBatch; ++i) {
-            const bool on = s0 + i < ns;
-            ls[i] = on ? pl[(s0 + i) * lstep] : -INFINITY;
-            v[i] = on ? *reinterpret_cast<const f32x4 *>(po + (s0 + i) * ostep) : f32x4{0.f, 0.f, 0.f, 0.f};
+            const int si = s0 + i * kCombineGroups;
+            const bool on = si < ns;
+            ls[i] = on ? pl[si * lstep] : -INFINITY;
+            v[i] = on ? *reinterpret_cast<const f32x4 *>(po + si * ostep) : f32x4{0.f, 0.f, 0.f, 0.f};
         }
         float mb = m;
 #pragma unroll
@@ -829,6 +838,35 @@ __global__ void __launch_bounds__(kCombineThreads) mla_decode_combine_kernel(con
             if (ls[i] != -INFINITY) acc += v[i] * wgt;              // (an empty piece holds zeros anyway)
         }
         m = mb;
+    }
+    // merge the groups: group 0 folds in the (m, sum, acc) of the others
+    if constexpr (kCombineGroups > 1) {
+        __shared__ f32x4 g_acc[kCombineGroups - 1][kCombineCols];
+        __shared__ float g_m[kCombineGroups - 1], g_sum[kCombineGroups - 1];
+        if (pg > 0) {
+            g_acc[pg - 1][t] = acc;
+            if (t == 0) {
+                g_m[pg - 1] = m;
+                g_sum[pg - 1] = sum;
+            }
+        }
+        __syncthreads();
+        if (pg > 0) return;
+        float mb = m;
+#pragma unroll
+        for (int i = 0; i < kCombineGroups - 1; ++i) mb = fmaxf(mb, g_m[i]);
+        if (mb != -INFINITY) {
+            const float keep = __builtin_amdgcn_exp2f(m - mb);
+            sum *= keep;
+            acc *= keep;
+#pragma unroll
+            for (int i = 0; i < kCombineGroups - 1; ++i) {
+                const float wgt = __builtin_amdgcn_exp2f(g_m[i] - mb);      // 0 for a group without pieces
+                sum += wgt * g_sum[i];
+                if (g_m[i] != -INFINITY) acc += g_acc[i][t] * wgt;
+            }
+            m = mb;
+        }
     }
     if (m == -INFINITY) {                     // a query token that sees no row at all (length < q_len)
         *reinterpret_cast<f32x4 *>(out) = f32x4{0.f, 0.f, 0.f, 0.f};
@@ -959,7 +997,11 @@ mla_status_t launch(const void *q, const void *kv_cache, int64_t kv_batch_stride
         if (hipGetLastError() != hipSuccess) return MLA_ERR_HIP;
     }
     if (flags & MLA_PHASE_COMBINE) {
-        hipLaunchKernelGGL(mla_decode_combine_kernel, dim3(batch * q_len * kHeads), dim3(kCombineThreads), 0, hs, p);
+        // pieces per sequence: about teams / batch, plus the two at its ends
+        if (teams / batch + 2 > 16)
+            hipLaunchKernelGGL(mla_decode_combine_kernel<kCombineWide>, dim3(batch * q_len * kHeads), dim3(kCombineCols * kCombineWide), 0, hs, p);
+        else
+            hipLaunchKernelGGL(mla_decode_combine_kernel<1>, dim3(batch * q_len * kHeads), dim3(kCombineCols), 0, hs, p);
         if (hipGetLastError() != hipSuccess) return MLA_ERR_HIP;
     }
     return MLA_OK;
