@@ -363,18 +363,22 @@ __global__ void __launch_bounds__(kThreads, 1) mla_decode_split_kernel(const Par
         for (int kk = 0; kk < kKSteps; ++kk) qf[kk] = qp[4 * kk];
     };
 
+    // The first tile is requested before q: loads come back in order, the tile is needed first (for
+    // the LDS write) and q only after it (for the first product), so q's trip overlaps that write.
     set_piece(u_lo);
-    load_q();
     if (w < n_tiles) issue_loads(w);
+    load_q();
     while (true) {
-        // this wavefront's tiles of the piece: w, w + 4, w + 8, ...; q and the first tile are on their way
+        // this wavefront's tiles of the piece: w, w + 4, w + 8, ...; the first tile and q are on their way
         int cur = w, nxt = w + kWaves;
-
-        // Q must be resident before the tile loop.  It was requested ahead of the first tile, so
-        // this waits for Q alone; left to the loop, the wait for Q would be re-evaluated on every
-        // tile with a count that also drains the prefetch of the next tile.
+        // Q must be resident before the first product.  It is waited for once, after the first tile
+        // has been written to LDS and before any load of the next tile is issued; left to the
+        // compiler, the wait would sit in the tile loop with a count that also drains the loads of
+        // the next tile.
+        auto wait_for_q = [&]() {
 #pragma unroll
-        for (int kk = 0; kk < kKSteps; ++kk) asm volatile("" : "+v"(qf[kk]));
+            for (int kk = 0; kk < kKSteps; ++kk) asm volatile("" : "+v"(qf[kk]));
+        };
 
         f32x4 o[kDvTiles];
 #pragma unroll
@@ -626,6 +630,7 @@ __global__ void __launch_bounds__(kThreads, 1) mla_decode_split_kernel(const Par
             while (cur < n_tiles) {
                 set_refill();
                 write_tile();
+                if (cur == w) wait_for_q();
                 process_tile(std::integral_constant<int, 3>{}, my + k_off, my + v_off, t_begin + cur * kTile);
                 cur = nxt;
                 nxt += kWaves;
@@ -640,6 +645,7 @@ __global__ void __launch_bounds__(kThreads, 1) mla_decode_split_kernel(const Par
                 // While the two tiles are worked on, the registers are refilled with this wavefront's next tile.
                 set_refill();
                 if (cur < n_tiles) write_tile();
+                if (base == 0) wait_for_q();
                 {
                     const int tb = t_begin + cur * kTile;
                     if (cur < n_tiles && tb < t_end) {               // own tile: staged, and visible to this token
@@ -679,8 +685,8 @@ __global__ void __launch_bounds__(kThreads, 1) mla_decode_split_kernel(const Par
             ++b;
             while (units_of(clamped_len(p, b)) == 0) ++b;   // empty sequences hold no units
             set_piece(first_unit);
-            load_q();
             if (w < n_tiles) issue_loads(w);
+            load_q();
         }
 
         // ---- a7: merge the four wavefronts, normalise, write (the epilogue of Algorithm 1) ----
