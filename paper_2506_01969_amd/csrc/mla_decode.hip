@@ -334,7 +334,7 @@ __global__ void __launch_bounds__(kThreads, 1) mla_decode_split_kernel(const Par
         n_tiles = stage_end > t_begin ? (stage_end - t_begin + kTile - 1) / kTile : 0;
         direct = (u_begin == 0 && u_end == ub);                // this team covers the whole sequence
         kv_b = p.kv + (long long)b * p.kv_batch_bytes;
-        row = (long long)b * p.q_len + j;
+        row = (long long)b * p.q_len + (has_token ? j : p.q_len - 1);   // a wavefront without a token reads a valid q and writes nothing
     };
 
     u32x4 st[kTileLoads];             // one tile in flight: 36 x 16 B per lane

@@ -400,17 +400,18 @@ def test_automatic_plan_follows_the_shape():
 
 
 def test_seeded_random_small_cases(oracle):
-    """Forty seeded draws of (batch, lengths, q_len, element type, number of workgroups): the piece
-    boundaries, tile tails and causal limits fall differently in each, at sizes the oracle finishes at once."""
+    """Two hundred seeded draws of (batch, lengths, q_len, element type, number of workgroups): the piece
+    boundaries, tile tails, causal limits and team shapes fall differently in each, at sizes the oracle
+    finishes at once."""
     rng = np.random.default_rng(20250601)
-    for case in range(40):
-        batch = int(rng.integers(1, 10))
-        q_len = int(rng.choice([1, 1, 2, 2, 3, 4]))
-        max_len = int(rng.choice([40, 130, 300, 900]))
+    for case in range(200):
+        batch = int(rng.integers(1, 12))
+        q_len = int(rng.choice([1, 1, 2, 2, 3, 4, 5, 8]))
+        max_len = int(rng.choice([33, 130, 300, 900, 2100]))
         lens = [int(x) for x in rng.integers(0, max_len + 1, size=batch)]
         if case % 5 == 0:
             lens[int(rng.integers(0, batch))] = max_len          # one sequence fills its allocation
-        num_wg = int(rng.integers(1, 41)) if case % 3 else None
+        num_wg = int(rng.integers(1, 300)) if case % 3 else None
         dtype = torch.float16 if case % 4 == 3 else torch.bfloat16
         q, kv, l = inputs.make_inputs(batch, max_len, lens, seed=7000 + case, poison_tail=True, q_len=q_len, dtype=dtype)
         ref_o, ref_l = _oracle_general(oracle, q, kv, l, dtype)
