@@ -421,13 +421,16 @@ def test_seeded_random_small_cases(oracle):
         if dtype == torch.float16:
             # One fp16 rounding of each probability: relative error 2^-12 / sqrt(3) rms per term, so an
             # output element is off by that times sqrt(sum_t w_t^2 v_t^2) rms: up to 1.4e-4 |v| when one
-            # or two rows carry all the weight, as in these short sequences (|v| is about 1 here).
+            # or two rows carry all the weight, as in these short sequences (|v| is about 1 here), and by
+            # at most 2^-12 max|v| (the weights sum to one).
             o, rl = ref_o.reshape(-1, 16, inputs.D_V), ref_l.reshape(-1, 16)
             assert np.isfinite(out).all(), label
             err = np.abs(out - o)
             fin = np.isfinite(rl)
             assert np.isneginf(lse[~fin]).all(), label
-            assert err.max() <= F16_MAX_ABS and math.sqrt(float((err ** 2).mean())) <= 1.5e-4, label
+            vals = kv[:, :, :inputs.D_V].float()
+            vmax = float(vals[torch.isfinite(vals)].abs().max())      # the rows past the lengths are NaN
+            assert err.max() <= 2.0 ** -12 * vmax + 1e-5 and math.sqrt(float((err ** 2).mean())) <= 1.5e-4, label
             assert not fin.any() or np.abs(lse[fin] - rl[fin]).max() <= F16_LSE, label
         else:
             _check(out, lse, ref_o.reshape(-1, 16, inputs.D_V), ref_l.reshape(-1, 16), label=label)
