@@ -124,3 +124,14 @@ def test_binding_rejects_host_tensors():
         mla.mla_decode(q, kv, lens, 0.1)
     with pytest.raises(TypeError):
         mla.mla_decode(q.float(), kv, lens, 0.1)
+
+
+def test_algorithmic_bytes_and_flops_of_the_headline_shape():
+    """The figures the roofline fraction is computed from: 1152 B per KV row read once for all 16 heads,
+    plus q (18,432 B), out (32,768 B), lse (64 B) and the length (4 B) per sequence; 2 (576 + 512) flop per
+    head and KV row."""
+    from paper_2506_01969_amd import inputs
+    lens = [65536] * 16
+    assert inputs.algorithmic_bytes(lens) == 1152 * 16 * 65536 + 51268 * 16 == 1208779840
+    assert inputs.algorithmic_flops(lens) == 2 * (576 + 512) * 16 * 16 * 65536 == 36507222016
+    assert inputs.algorithmic_bytes([1, 0, 7]) == 1152 * 8 + 51268 * 3
