@@ -10,8 +10,8 @@
  *
  * On the device the KV rows of all sequences form one stream of 128-token units
  * that is divided evenly over a persistent grid of workgroups (so ragged batches
- * are balanced, and results are bit-identical from run to run); each workgroup runs the block-wise online-softmax recurrence of
- * Algorithm 1 on its pieces in the transposed orientation of equations (1)-(4)
+ * are balanced, and results are bit-identical from run to run); each workgroup
+ * runs the block-wise online-softmax recurrence of Algorithm 1 on its pieces in the transposed orientation of equations (1)-(4)
  * (KV tokens on the matrix-core M axis), and a second kernel merges, by
  * log-sum-exp, the pieces of every sequence that several workgroups shared.  The
  * paper has no split over KV; the merge is the same m / l recurrence applied
@@ -39,7 +39,7 @@ extern "C" {
 typedef enum {
     MLA_OK = 0,
     MLA_ERR_INVALID_ARG = 1,         /* null / misaligned pointer, negative size or stride      */
-    MLA_ERR_UNSUPPORTED_SHAPE = 2,   /* anything but 16 heads, d_qk 576, d_v 512, q_len 1       */
+    MLA_ERR_UNSUPPORTED_SHAPE = 2,   /* anything but 16 heads, d_qk 576, d_v 512, q_len 1 .. 8  */
     MLA_ERR_WORKSPACE_TOO_SMALL = 3, /* workspace_bytes below mla_decode_workspace_size()       */
     MLA_ERR_HIP = 4                  /* a HIP runtime call or a kernel launch failed            */
 } mla_status_t;

@@ -1105,7 +1105,7 @@ const char *mla_status_string(mla_status_t status) {
     switch (status) {
         case MLA_OK: return "ok";
         case MLA_ERR_INVALID_ARG: return "invalid argument";
-        case MLA_ERR_UNSUPPORTED_SHAPE: return "unsupported shape (need 16 heads, d_qk 576, d_v 512, q_len 1)";
+        case MLA_ERR_UNSUPPORTED_SHAPE: return "unsupported shape (need 16 heads, d_qk 576, d_v 512, q_len 1 to 8; direct orientation: bf16, q_len 1)";
         case MLA_ERR_WORKSPACE_TOO_SMALL: return "workspace too small";
         case MLA_ERR_HIP: return "HIP runtime error";
     }
