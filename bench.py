@@ -184,7 +184,8 @@ def main():
     achieved_gbps = alg_bytes / (split_ms_avg * 1e-3) / 1e9
 
     traffic = None
-    if args.config == 4 and args.dtype == "bf16" and os.path.exists(TRAFFIC_FILE):
+    if (args.config == 4 and args.dtype == "bf16" and args.q_len == 1 and args.orientation != "direct"
+            and not args.workgroups and os.path.exists(TRAFFIC_FILE)):   # the counters were read for this launch only
         try:
             traffic = json.load(open(TRAFFIC_FILE)).get("hbm_bytes_per_launch")
         except (OSError, ValueError):
