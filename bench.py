@@ -64,34 +64,6 @@ def sweep(torch, inputs, mla, dev, args):
             del kvs
 
 
-def error_report(torch, inputs, mla, dev):
-    """Numerical error against the fp64 oracle in the manner of the paper's Table 1 (Section 4.3: RMSE of
-    the FP16 outputs against a double-precision reference), for both input types over the five benchmark
-    configurations.  The library's outputs are fp32; the paper's kernels deliver FP16, so the error of the
-    output rounded to the input type is given as well."""
-    import math
-    import numpy as np
-    from oracle import mla_oracle
-    for name, dt, tag in (("fp16", torch.float16, mla_oracle.F16), ("bf16", torch.bfloat16, mla_oracle.BF16)):
-        for cfg in sorted(inputs.CONFIGS):
-            q, kv, lens = inputs.make_config(cfg, dtype=dt)
-            out, lse = mla.mla_decode(q.to(dev), kv.to(dev), lens.to(dev), inputs.SCALE)
-            torch.cuda.synchronize()
-            ref_o, ref_l = mla_oracle.decode_general(inputs.bits16(q), inputs.bits16(kv), lens.numpy(), inputs.SCALE,
-                                                     inputs.D_V, dtype=tag)
-            ref_o = ref_o.reshape(out.shape[0], 16, 512)
-            o32 = out.cpu().reshape(out.shape[0], 16, 512)
-            e32 = o32.numpy().astype(np.float64) - ref_o
-            e16 = o32.to(dt).float().numpy().astype(np.float64) - ref_o
-            print(json.dumps({"dtype": name, "config": cfg, "batch": int(out.shape[0]), "total_kv_tokens": int(lens.sum()),
-                              "rmse_fp32_out": math.sqrt(float((e32 ** 2).mean())), "max_abs_fp32_out": float(np.abs(e32).max()),
-                              "rmse_out_rounded_to_input_type": math.sqrt(float((e16 ** 2).mean())),
-                              "rms_of_reference_out": math.sqrt(float((ref_o ** 2).mean())),
-                              "max_abs_lse": float(np.abs(lse.cpu().numpy().reshape(-1, 16) - ref_l.reshape(-1, 16)).max())}),
-                  flush=True)
-            del q, kv, out
-
-
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -110,9 +82,6 @@ def main():
     ap.add_argument("--sweep", action="store_true",
                     help="time the whole call over batch 16 and 32 x KV length 512 ... 64K (the grid of the "
                          "paper's Figure 1) and print one JSON line per point instead of the benchmark line")
-    ap.add_argument("--error-report", action="store_true",
-                    help="print the numerical error against the fp64 oracle (RMSE as in the paper's Table 1) of "
-                         "both input types over the five benchmark configurations, one JSON line each, and exit")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="only run a plain device-to-device copy of 1 GiB five times (counter calibration "
                          "for rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE) and exit")
@@ -144,10 +113,6 @@ def main():
 
     if args.sweep:
         sweep(torch, inputs, mla, dev, args)
-        return
-
-    if args.error_report:
-        error_report(torch, inputs, mla, dev)
         return
 
     cfg = inputs.CONFIGS[args.config]
