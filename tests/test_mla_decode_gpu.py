@@ -367,6 +367,18 @@ def test_two_query_tokens_headline_shape(oracle):
     _check(out, lse, ref_o.reshape(-1, 16, inputs.D_V), ref_l.reshape(-1, 16), label="q_len=2 headline")
 
 
+def test_two_query_tokens_ragged_config(oracle):
+    """Configuration 5 (batch 32, lengths 1024 ... 65536) with two query tokens: pieces that cross
+    sequence boundaries at full size, in the launch configuration of the automatic plan."""
+    print("case q_len 2 config 5 generating", flush=True)
+    q, kv, l = inputs.make_config(5, poison_tail=True, q_len=2)
+    print("case q_len 2 config 5 gpu", flush=True)
+    out, lse = _run_general(q, kv, l)
+    print("case q_len 2 config 5 oracle", flush=True)
+    ref_o, ref_l = _oracle_general(oracle, q, kv, l, torch.bfloat16)
+    _check(out, lse, ref_o.reshape(-1, 16, inputs.D_V), ref_l.reshape(-1, 16), label="q_len=2 config 5")
+
+
 def test_two_query_tokens_repeat_is_bit_identical_and_workspace_contents_do_not_matter():
     """The wavefront pairs read each other's LDS tiles between barriers; the result must not depend on
     timing or on what the workspace held (0xFF.. is NaN as fp32)."""
