@@ -31,8 +31,8 @@ def sweep(torch, inputs, mla, dev, args):
     these shapes is the job of the tests).  KV buffers are rotated so that consecutive calls cannot be
     served from the 256 MB last-level cache."""
     g = torch.Generator(device=dev).manual_seed(inputs.BASE_SEED)
-    for batch in (16, 32):
-        for n in (512, 1024, 2048, 4096, 8192, 16384, 32768, 65536):
+    for batch in [int(x) for x in args.batches.split(",")]:
+        for n in [int(x) for x in args.kv_lens.split(",")]:
             kv_bytes = batch * n * inputs.D_QK * 2
             n_buf = max(2, min(64, -(-(512 << 20) // kv_bytes)))
             dt = torch.float16 if args.dtype == "fp16" else torch.bfloat16
@@ -82,6 +82,8 @@ def main():
     ap.add_argument("--sweep", action="store_true",
                     help="time the whole call over batch 16 and 32 x KV length 512 ... 64K (the grid of the "
                          "paper's Figure 1) and print one JSON line per point instead of the benchmark line")
+    ap.add_argument("--batches", default="16,32", help="batch sizes of --sweep")
+    ap.add_argument("--kv-lens", default="512,1024,2048,4096,8192,16384,32768,65536", help="KV lengths of --sweep")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="only run a plain device-to-device copy of 1 GiB five times (counter calibration "
                          "for rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE) and exit")
