@@ -781,23 +781,29 @@ __global__ void __launch_bounds__(kThreads, 1) mla_decode_split_kernel(const Par
 // Combine kernel (step a8): per (sequence, head), merge the partial results of the workgroups
 // that shared the sequence by log-sum-exp: the m / l recurrence of Algorithm 1 applied across
 // workgroups instead of KV blocks.  The set of workgroups follows from the same partition.
-template <int kCombineGroups>
-__global__ void __launch_bounds__(kCombineCols * kCombineGroups) mla_decode_combine_kernel(const Params p) {
-    const int row = blockIdx.x / kHeads;      // (sequence, query token)
-    const int h = blockIdx.x - row * kHeads;
+// kCombineGroups thread groups take the pieces in turn; the 512 value columns are divided over
+// kCombineSlices blocks (a block is one compute unit's worth of memory intake: with hundreds of pieces
+// per sequence and few sequences, one block per (sequence, head) would read 2 KB per piece alone).
+template <int kCombineGroups, int kCombineSlices>
+__global__ void __launch_bounds__(kCombineCols * kCombineGroups / kCombineSlices) mla_decode_combine_kernel(const Params p) {
+    constexpr int kGroupThreads = kCombineCols / kCombineSlices;   // threads of a group, 4 columns each
+    const int rh = blockIdx.x / kCombineSlices;
+    const int slice = blockIdx.x - rh * kCombineSlices;
+    const int row = rh / kHeads;              // (sequence, query token)
+    const int h = rh - row * kHeads;
     const int b = row / p.q_len;
     const int j = row - b * p.q_len;
-    const int t = threadIdx.x & (kCombineCols - 1);   // 128 threads x 4 columns
-    const int pg = threadIdx.x / kCombineCols;        // group of pieces (wave-uniform)
+    const int t = threadIdx.x % kGroupThreads;        // thread within its group
+    const int pg = threadIdx.x / kGroupThreads;       // group of pieces
+    const int col = (slice * kGroupThreads + t) * 4;  // this thread's four columns
+    const bool writes_lse = (slice == 0 && threadIdx.x == 0);
     int total_units, seq_first;
-    unit_sums(p, t & 63, b, total_units, seq_first);
+    unit_sums(p, threadIdx.x & 63, b, total_units, seq_first);
     const int ub = units_of(clamped_len(p, b));
-    float *out = p.out + ((long long)row * kHeads + h) * kDv + t * 4;
+    float *out = p.out + ((long long)row * kHeads + h) * kDv + col;
     if (ub == 0) {                            // empty sequence
-        if (pg == 0) {
-            *reinterpret_cast<f32x4 *>(out) = f32x4{0.f, 0.f, 0.f, 0.f};
-            if (t == 0) p.lse[row * kHeads + h] = -INFINITY;
-        }
+        if (pg == 0) *reinterpret_cast<f32x4 *>(out) = f32x4{0.f, 0.f, 0.f, 0.f};
+        if (writes_lse) p.lse[row * kHeads + h] = -INFINITY;
         return;
     }
     const int active = total_units < p.num_wg ? total_units : p.num_wg;    // as in the main kernel
@@ -810,7 +816,7 @@ __global__ void __launch_bounds__(kCombineCols * kCombineGroups) mla_decode_comb
     const int lstep = p.q_len * kHeads;
     const long long ostep = (long long)p.q_len * kHeads * kDv;
     const float *pl = p.part_lse + first_slot * kHeads + h;
-    const float *po = p.part_out + (first_slot * kHeads + h) * kDv + t * 4;
+    const float *po = p.part_out + (first_slot * kHeads + h) * kDv + col;
     // The kernel is a chain of memory round trips, so the pieces are dealt to the block's thread
     // groups in turn (one group, or four when the host expects more than kBatch pieces per sequence:
     // few sequences over many workgroups), and each group issues every load of up to kBatch of its pieces (their
@@ -847,7 +853,7 @@ __global__ void __launch_bounds__(kCombineCols * kCombineGroups) mla_decode_comb
     }
     // merge the groups: group 0 folds in the (m, sum, acc) of the others
     if constexpr (kCombineGroups > 1) {
-        __shared__ f32x4 g_acc[kCombineGroups - 1][kCombineCols];
+        __shared__ f32x4 g_acc[kCombineGroups - 1][kGroupThreads];
         __shared__ float g_m[kCombineGroups - 1], g_sum[kCombineGroups - 1];
         if (pg > 0) {
             g_acc[pg - 1][t] = acc;
@@ -876,13 +882,13 @@ __global__ void __launch_bounds__(kCombineCols * kCombineGroups) mla_decode_comb
     }
     if (m == -INFINITY) {                     // a query token that sees no row at all (length < q_len)
         *reinterpret_cast<f32x4 *>(out) = f32x4{0.f, 0.f, 0.f, 0.f};
-        if (t == 0) p.lse[row * kHeads + h] = -INFINITY;
+        if (writes_lse) p.lse[row * kHeads + h] = -INFINITY;
         return;
     }
     const float tot = m + __builtin_amdgcn_logf(sum);
     acc *= 1.0f / sum;
     *reinterpret_cast<f32x4 *>(out) = acc;
-    if (t == 0) p.lse[row * kHeads + h] = tot * 0.6931471805599453f;
+    if (writes_lse) p.lse[row * kHeads + h] = tot * 0.6931471805599453f;
 }
 
 // ---- host side ---------------------------------------------------------------------------------
@@ -1005,9 +1011,9 @@ mla_status_t launch(const void *q, const void *kv_cache, int64_t kv_batch_stride
     if (flags & MLA_PHASE_COMBINE) {
         // pieces per sequence: about teams / batch, plus the two at its ends
         if (teams / batch + 2 > 16)
-            hipLaunchKernelGGL(mla_decode_combine_kernel<kCombineWide>, dim3(batch * q_len * kHeads), dim3(kCombineCols * kCombineWide), 0, hs, p);
+            hipLaunchKernelGGL((mla_decode_combine_kernel<kCombineWide, kCombineWide>), dim3(batch * q_len * kHeads * kCombineWide), dim3(kCombineCols), 0, hs, p);
         else
-            hipLaunchKernelGGL(mla_decode_combine_kernel<1>, dim3(batch * q_len * kHeads), dim3(kCombineCols), 0, hs, p);
+            hipLaunchKernelGGL((mla_decode_combine_kernel<1, 1>), dim3(batch * q_len * kHeads), dim3(kCombineCols), 0, hs, p);
         if (hipGetLastError() != hipSuccess) return MLA_ERR_HIP;
     }
     return MLA_OK;
