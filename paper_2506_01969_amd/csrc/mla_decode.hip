@@ -910,7 +910,7 @@ inline Plan plan_for(int q_len, int num_wg, bool direct_orientation) {
     return pl;
 }
 
-inline size_t workspace_bytes_for(int batch, int num_wg) {
+constexpr size_t workspace_bytes_for(int batch, int num_wg) {
     // One partial slot per (team, sequence, query token) that can occur: (teams + sequences) x q_len.
     // `batch` counts sequences x tokens.  A team is one or more workgroups and a workgroup takes at
     // most kMaxShare tokens, so teams x q_len <= kMaxShare x num_wg, or q_len (one team) if larger.
@@ -947,6 +947,14 @@ mla_status_t validate(const void *q, const void *kv_cache, int64_t kv_batch_stri
     if (kv_batch_stride < (int64_t)max_seqlen_kv * kDqk || (kv_batch_stride & 7) != 0) return MLA_ERR_INVALID_ARG;
     if (!(scale == scale) || std::isinf(scale)) return MLA_ERR_INVALID_ARG;
     return MLA_OK;
+}
+
+// The launch call's own return value says whether THIS launch was accepted; hipGetLastError() would
+// also report (and clear) an error left behind by an earlier, unrelated runtime call of the thread.
+hipError_t launch_kernel(const void *fn, int blocks, int threads, size_t lds_bytes, hipStream_t stream, const Params &p) {
+    Params copy = p;
+    void *args[] = {&copy};
+    return hipLaunchKernel(fn, dim3(blocks), dim3(threads), args, lds_bytes, stream);
 }
 
 // Everything below runs only after validate() passed.
@@ -1005,16 +1013,15 @@ mla_status_t launch(const void *q, const void *kv_cache, int64_t kv_batch_stride
     hipStream_t hs = static_cast<hipStream_t>(stream);
     if (flags & MLA_PHASE_SPLIT) {
         const int team_stride = plan.members > 1 ? (teams + 7) / 8 * 8 : teams;   // see the kernel: a team behind one L2
-        hipLaunchKernelGGL(split_fn, dim3(team_stride * plan.members), dim3(kThreads), kLdsBytes, hs, p);
-        if (hipGetLastError() != hipSuccess) return MLA_ERR_HIP;
+        if (launch_kernel(reinterpret_cast<const void *>(split_fn), team_stride * plan.members, kThreads, kLdsBytes, hs, p) != hipSuccess)
+            return MLA_ERR_HIP;
     }
     if (flags & MLA_PHASE_COMBINE) {
         // pieces per sequence: about teams / batch, plus the two at its ends
-        if (teams / batch + 2 > 16)
-            hipLaunchKernelGGL((mla_decode_combine_kernel<kCombineWide, kCombineWide>), dim3(batch * q_len * kHeads * kCombineWide), dim3(kCombineCols), 0, hs, p);
-        else
-            hipLaunchKernelGGL((mla_decode_combine_kernel<1, 1>), dim3(batch * q_len * kHeads), dim3(kCombineCols), 0, hs, p);
-        if (hipGetLastError() != hipSuccess) return MLA_ERR_HIP;
+        const bool wide = teams / batch + 2 > 16;
+        const kernel_fn combine_fn = wide ? mla_decode_combine_kernel<kCombineWide, kCombineWide> : mla_decode_combine_kernel<1, 1>;
+        if (launch_kernel(reinterpret_cast<const void *>(combine_fn), batch * q_len * kHeads * (wide ? kCombineWide : 1), kCombineCols, 0, hs, p) != hipSuccess)
+            return MLA_ERR_HIP;
     }
     return MLA_OK;
 }
