@@ -41,7 +41,8 @@ typedef enum {
     MLA_ERR_INVALID_ARG = 1,         /* null / misaligned pointer, negative size or stride      */
     MLA_ERR_UNSUPPORTED_SHAPE = 2,   /* anything but 16 heads, d_qk 576, d_v 512, q_len 1 .. 8  */
     MLA_ERR_WORKSPACE_TOO_SMALL = 3, /* workspace_bytes below mla_decode_workspace_size()       */
-    MLA_ERR_HIP = 4                  /* a HIP runtime call or a kernel launch failed            */
+    MLA_ERR_HIP = 4,                 /* a HIP runtime call or a kernel launch failed            */
+    MLA_ERR_STATIC_LIMIT = 5         /* mla_decode_static(): beyond the static workspace        */
 } mla_status_t;
 
 /* Fixed problem shape (DeepSeek-R1 share of one GPU, Section 4.1). */
@@ -174,6 +175,28 @@ mla_status_t mla_decode_typed(const void *q, const void *kv_cache, int64_t kv_ba
  */
 mla_status_t mla_decode_planned_workgroups(int batch, int q_len, int max_seqlen_kv,
                                            int *num_workgroups);
+
+/*
+ * The call for callers that cannot allocate device memory or bring a workspace: code under HIP
+ * graph capture, tight serving loops, harnesses that forbid hipMalloc.  It is mla_decode_typed()
+ * with the automatic plan and both phases, and with the partial results kept in a file-scope
+ * device array of the library (19.2 MB per GPU, held until the process ends) instead of a caller's
+ * workspace.  It calls no allocating routine.  The same kernels run, so the results are bit for bit
+ * those of mla_decode_typed(..., num_workgroups = 0, MLA_PHASE_SPLIT | MLA_PHASE_COMBINE).
+ *
+ * Limits: batch * q_len <= MLA_STATIC_MAX_ROWS and a device of at most MLA_STATIC_MAX_WORKGROUPS
+ * compute units; beyond either, MLA_ERR_STATIC_LIMIT is returned before anything is launched.
+ * Every call on a GPU shares that GPU's array: calls on one GPU must be ordered (one stream, or
+ * events between streams); calls that overlap on one GPU race on the partial results.  The array's
+ * contents never need clearing: every slot the merge reads was written by the same call.
+ * All other arguments, layouts and error behaviour are those of mla_decode_typed().
+ */
+#define MLA_STATIC_MAX_ROWS 64
+#define MLA_STATIC_MAX_WORKGROUPS 256
+mla_status_t mla_decode_static(const void *q, const void *kv_cache, int64_t kv_batch_stride,
+                               const int32_t *cache_seqlens, int batch, int q_len, int num_heads,
+                               int max_seqlen_kv, int dtype, float scale, float *out, float *lse,
+                               void *stream);
 
 /* Static string for a status code (never NULL). */
 const char *mla_status_string(mla_status_t status);

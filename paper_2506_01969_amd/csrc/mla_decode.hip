@@ -922,6 +922,13 @@ constexpr size_t workspace_bytes_for(int batch, int num_wg) {
 
 constexpr int kMaxWorkgroups = 1 << 16;
 
+// Workspace of mla_decode_static(): for callers that cannot allocate.  Sized for the automatic plan
+// on up to MLA_STATIC_MAX_WORKGROUPS compute units and MLA_STATIC_MAX_ROWS (sequence, query token)
+// rows: 19.2 MB that every GPU the library runs on holds until the process ends.  In host code the
+// array's name is only a handle for hipGetSymbolAddress(); kernels get the device address it returns.
+constexpr size_t kStaticBytes = workspace_bytes_for(MLA_STATIC_MAX_ROWS, MLA_STATIC_MAX_WORKGROUPS);
+static __device__ __align__(256) unsigned char scratch[kStaticBytes];
+
 bool misaligned(const void *ptr) { return (reinterpret_cast<uintptr_t>(ptr) & 15u) != 0; }
 
 constexpr int kMaxQLen = MLA_MAX_Q_LEN;
@@ -1108,6 +1115,39 @@ mla_status_t mla_decode(const void *q, const void *kv_cache, int64_t kv_batch_st
                          out, lse, workspace, workspace_bytes, 0, MLA_PHASE_SPLIT | MLA_PHASE_COMBINE, stream);
 }
 
+mla_status_t mla_decode_static(const void *q, const void *kv_cache, int64_t kv_batch_stride,
+                               const int32_t *cache_seqlens, int batch, int q_len, int num_heads,
+                               int max_seqlen_kv, int dtype, float scale, float *out, float *lse,
+                               void *stream) {
+    if (dtype != MLA_DTYPE_BF16 && dtype != MLA_DTYPE_F16) return MLA_ERR_INVALID_ARG;
+    if (batch <= 0 || batch > (1 << 20)) return MLA_ERR_INVALID_ARG;
+    if (q_len < 1 || q_len > kMaxQLen) return MLA_ERR_UNSUPPORTED_SHAPE;
+    // the device address of this GPU's copy of the array, looked up once per device
+    static std::mutex mu;
+    static void *scratch_ptr[64] = {};
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return MLA_ERR_HIP;
+    void *ws = nullptr;
+    {
+        std::lock_guard<std::mutex> lock(mu);
+        if (!scratch_ptr[dev]) {
+            void *ptr = nullptr;
+            if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) return MLA_ERR_HIP;
+            scratch_ptr[dev] = ptr;
+        }
+        ws = scratch_ptr[dev];
+    }
+    mla_status_t st = validate(q, kv_cache, kv_batch_stride, cache_seqlens, batch * q_len, num_heads,
+                               max_seqlen_kv, scale, out, lse, ws);
+    if (st != MLA_OK) return st;
+    int num_wg = 0;
+    st = planned_workgroups(batch, q_len, max_seqlen_kv, &num_wg, nullptr);
+    if (st != MLA_OK) return st;
+    if (batch * q_len > MLA_STATIC_MAX_ROWS || num_wg > MLA_STATIC_MAX_WORKGROUPS) return MLA_ERR_STATIC_LIMIT;
+    return launch(q, kv_cache, kv_batch_stride, cache_seqlens, batch, q_len, max_seqlen_kv, scale, out, lse,
+                  ws, kStaticBytes, num_wg, MLA_PHASE_SPLIT | MLA_PHASE_COMBINE, dtype, stream);
+}
+
 mla_status_t mla_decode_planned_workgroups(int batch, int q_len, int max_seqlen_kv, int *num_workgroups) {
     if (!num_workgroups || batch <= 0 || max_seqlen_kv <= 0) return MLA_ERR_INVALID_ARG;
     if (q_len < 1 || q_len > kMaxQLen) return MLA_ERR_UNSUPPORTED_SHAPE;
@@ -1121,6 +1161,7 @@ const char *mla_status_string(mla_status_t status) {
         case MLA_ERR_UNSUPPORTED_SHAPE: return "unsupported shape (need 16 heads, d_qk 576, d_v 512, q_len 1 to 8; direct orientation: bf16, q_len 1)";
         case MLA_ERR_WORKSPACE_TOO_SMALL: return "workspace too small";
         case MLA_ERR_HIP: return "HIP runtime error";
+        case MLA_ERR_STATIC_LIMIT: return "too large for the library's static workspace (mla_decode_static: batch * q_len <= 64, <= 256 compute units)";
     }
     return "unknown status";
 }

@@ -20,6 +20,7 @@ MLA_ERR_INVALID_ARG = 1
 MLA_ERR_UNSUPPORTED_SHAPE = 2
 MLA_ERR_WORKSPACE_TOO_SMALL = 3
 MLA_ERR_HIP = 4
+MLA_ERR_STATIC_LIMIT = 5
 
 LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libmla_decode.so")
 _lib = None
@@ -54,6 +55,8 @@ def lib():
         L.mla_decode_typed.argtypes = [vp, vp, ctypes.c_int64, vp, ci, ci, ci, ci, ci, ctypes.c_float, vp, vp,
                                        vp, sz, ci, ci, vp]
         L.mla_decode_typed.restype = ci
+        L.mla_decode_static.argtypes = [vp, vp, ctypes.c_int64, vp, ci, ci, ci, ci, ci, ctypes.c_float, vp, vp, vp]
+        L.mla_decode_static.restype = ci
         L.mla_decode_planned_workgroups.argtypes = [ci, ci, ci, cip]
         L.mla_decode_planned_workgroups.restype = ci
         L.mla_status_string.argtypes = [ci]
@@ -149,4 +152,23 @@ def mla_decode(q, kv_cache, cache_seqlens, scale, out=None, lse=None, workspace=
         where = "mla_decode_ex"
     if st != MLA_OK:
         raise MlaError(st, where)
+    return out, lse
+
+
+def mla_decode_static(q, kv_cache, cache_seqlens, scale, out, lse):
+    """``mla_decode_static`` of the C ABI: the automatic plan with the library's own static workspace,
+    for callers that cannot allocate.  ``out`` and ``lse`` are the caller's; nothing is allocated here."""
+    _check_tensors(q, kv_cache, cache_seqlens)
+    batch, q_len, heads, _ = q.shape
+    if out.dtype != torch.float32 or lse.dtype != torch.float32 or not (out.is_contiguous() and lse.is_contiguous()):
+        raise TypeError("out and lse must be contiguous fp32 tensors")
+    if out.numel() != batch * q_len * heads * D_V or lse.numel() != batch * q_len * heads:
+        raise ValueError("out must hold [batch, q_len, heads, 512] and lse [batch, q_len, heads]")
+    stream = ctypes.c_void_p(torch.cuda.current_stream(q.device).cuda_stream)
+    st = lib().mla_decode_static(ctypes.c_void_p(q.data_ptr()), ctypes.c_void_p(kv_cache.data_ptr()), kv_cache.stride(0),
+                                 ctypes.c_void_p(cache_seqlens.data_ptr()), batch, q_len, heads, kv_cache.shape[1],
+                                 DTYPE_F16 if q.dtype == torch.float16 else DTYPE_BF16, float(scale),
+                                 ctypes.c_void_p(out.data_ptr()), ctypes.c_void_p(lse.data_ptr()), stream)
+    if st != MLA_OK:
+        raise MlaError(st, "mla_decode_static")
     return out, lse

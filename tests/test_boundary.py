@@ -29,8 +29,8 @@ def test_library_exports_every_declared_symbol():
 
 def test_status_strings():
     lib = mla.lib()
-    seen = {lib.mla_status_string(i) for i in range(5)}
-    assert len(seen) == 5 and all(seen)
+    seen = {lib.mla_status_string(i) for i in range(6)}
+    assert len(seen) == 6 and all(seen)
     assert lib.mla_status_string(99)
 
 
