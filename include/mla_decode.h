@@ -119,12 +119,20 @@ mla_status_t mla_decode(const void *q, const void *kv_cache, int64_t kv_batch_st
  *                   same result up to fp32 summation order, kept so that the two orientations can
  *                   be measured against each other.  bf16 and one query token only
  *                   (else MLA_ERR_UNSUPPORTED_SHAPE).
+ *                   MLA_UNIT_FINE / MLA_UNIT_COARSE (at most one) force the unit of the stream to
+ *                   MLA_UNIT_TOKENS_FINE / MLA_UNIT_TOKENS rows.  Without either the unit is 128
+ *                   rows (one 32-row tile for each of a workgroup's four wavefronts) unless
+ *                   batch * ceil(max_seqlen_kv / 128) is below the number of workgroups: such a short
+ *                   stream is divided by the tile, so that it spreads over more compute units.
  * All other arguments, and all error behaviour, are those of mla_decode().
  */
 #define MLA_UNIT_TOKENS 128
+#define MLA_UNIT_TOKENS_FINE 32
 #define MLA_PHASE_SPLIT 1
 #define MLA_PHASE_COMBINE 2
 #define MLA_ORIENT_DIRECT 8
+#define MLA_UNIT_FINE 16
+#define MLA_UNIT_COARSE 32
 mla_status_t mla_decode_ex(const void *q, const void *kv_cache, int64_t kv_batch_stride,
                            const int32_t *cache_seqlens, int batch, int num_heads,
                            int max_seqlen_kv, float scale, float *out, float *lse,
@@ -175,6 +183,25 @@ mla_status_t mla_decode_typed(const void *q, const void *kv_cache, int64_t kv_ba
  */
 mla_status_t mla_decode_planned_workgroups(int batch, int q_len, int max_seqlen_kv,
                                            int *num_workgroups);
+
+/*
+ * The partition of a batch as the kernels derive it on the device, as a table (tests, diagnosis).
+ * Launches one small kernel on `stream` that evaluates the same device functions as the two kernels
+ * of mla_decode_typed() called with the same batch, q_len, max_seqlen_kv, num_workgroups and flags
+ * (MLA_ORIENT_DIRECT and the MLA_UNIT_ flags matter; phases are ignored), and writes 8 int32 per
+ * record into `table` (device, (num_workgroups + batch) * 8 int32 or more; with num_workgroups == 0,
+ * size it with mla_decode_planned_workgroups()):
+ *   record k < *teams        {total units, active teams, first unit, end unit, first sequence, that
+ *                             sequence's first unit, 0, 0} of team k (the middle four -1 if idle)
+ *   record *teams + b        {total units, first unit, units, first team, last team, 0, 0, 0} of
+ *                             sequence b (teams -1 for an empty sequence)
+ * *teams (host) receives the number of teams (workgroups per query-token pair) the unit stream is
+ * divided over and *unit_tokens (host) the rows per unit.  The split over the KV length is not in the
+ * paper; see mla_decode_typed().  Errors as for mla_decode_typed(), before anything is launched.
+ */
+mla_status_t mla_decode_plan_table(const int32_t *cache_seqlens, int batch, int q_len, int max_seqlen_kv,
+                                   int num_workgroups, int flags, int32_t *table, int *teams,
+                                   int *unit_tokens, void *stream);
 
 /*
  * The call for callers that cannot allocate device memory or bring a workspace: code under HIP

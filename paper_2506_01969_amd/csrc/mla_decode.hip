@@ -57,6 +57,7 @@
 #include <type_traits>
 
 #include "mla_decode.h"
+#include "mla_plan.h"
 
 namespace {
 
@@ -71,14 +72,16 @@ constexpr int kThreads = kWaves * 64;
 constexpr int kWaveLds = kTile * kLdsRow;    // 37,376 B private tile per wavefront
 constexpr int kTileLoads = kTile * kRowBytes / 1024;   // 36 loads of 64 lanes x 16 B per tile
 static_assert(kTileLoads * 1024 == kTile * kRowBytes, "a tile must be a whole number of 1 KB pieces");
+static_assert(kRowBytes == mla_plan::kRowBytes && kTile == mla_plan::kTileRows && kTileLoads == mla_plan::kTileLoads,
+              "the plan header and the kernel disagree on the tile");
 constexpr int kKSteps = kDqk / 32;           // 18 MFMA k-steps over the 576 dims
 constexpr int kDvTiles = kDv / 16;           // 32 output tiles of 16 value columns
 constexpr int kStatsOff = kWaves * kWaveLds; // m and l of the 4 wavefronts live after the tiles
 constexpr int kRescaleOff = kStatsOff + 2 * kWaves * kHeads * 4;  // 2 KB per wavefront, cold rescale path
 constexpr int kLdsBytes = kRescaleOff + kWaves * 2048;
 static_assert(kLdsBytes <= 160 * 1024, "LDS of one compute unit");
-constexpr int kUnit = kWaves * kTile;          // 128 tokens: the scheduling unit (one tile per wavefront)
-static_assert(kUnit == MLA_UNIT_TOKENS, "header and kernel disagree on the scheduling unit");
+static_assert(kWaves * kTile == MLA_UNIT_TOKENS && mla_plan::kUnitCoarse == MLA_UNIT_TOKENS && mla_plan::kUnitFine == MLA_UNIT_TOKENS_FINE,
+              "header and kernel disagree on the scheduling units");
 constexpr int kCombineCols = 128;               // threads that cover the 512 value columns, 4 each
 constexpr int kCombineWide = 4;                 // groups of such threads per block when a sequence has many pieces
 constexpr int kSchedMfma = 0x008;              // instruction classes of sched_group_barrier
@@ -108,23 +111,15 @@ struct Params {
     int q_len;                // query tokens per sequence
     int max_seqlen;
     int num_wg;               // G: teams (one workgroup per two query tokens) the unit stream is divided over
+    int unit;                 // KV rows per unit of the stream: 128, or 32 for a short stream
     float scale_log2e;        // scale * log2(e): scores are kept in the base-2 domain
 };
 
-__device__ __forceinline__ int clamped_len(const Params &p, int b) {
-    const int n = p.seqlens[b];
-    return n < 0 ? 0 : (n > p.max_seqlen ? p.max_seqlen : n);
-}
+// The integer rules of the partition (units, ranges, slots, tile offsets) live in mla_plan.h, shared
+// with the host code and the CPU tests; below are only their wave-parallel evaluations.
+__device__ __forceinline__ int clamped_len(const Params &p, int b) { return mla_plan::clamp_len(p.seqlens[b], p.max_seqlen); }
 
-// KV rows that query token j of a sequence of n rows attends to.  With q_len query tokens per
-// sequence the new tokens are the last q_len rows of the cache and attention is causal among them:
-// token j sees all but the last q_len - 1 - j rows.
-__device__ __forceinline__ int visible_len(const Params &p, int n, int j) {
-    const int v = n - (p.q_len - 1 - j);
-    return v < 0 ? 0 : v;
-}
-
-__device__ __forceinline__ int units_of(int n) { return (n + kUnit - 1) / kUnit; }
+__device__ __forceinline__ int units_at(const Params &p, int b) { return mla_plan::units_of(clamped_len(p, b), p.unit); }
 
 __device__ __forceinline__ int wave_sum(int v) {
 #pragma unroll
@@ -139,7 +134,7 @@ __device__ __forceinline__ void unit_sums(const Params &p, int lane, int b, int 
     int tot = 0, bef = 0;
     for (int base = 0; base < p.batch; base += 64) {
         const int i = base + lane;
-        const int u = i < p.batch ? units_of(clamped_len(p, i)) : 0;
+        const int u = i < p.batch ? units_at(p, i) : 0;
         tot += u;
         bef += i < b ? u : 0;
     }
@@ -153,7 +148,7 @@ __device__ __forceinline__ void locate_unit(const Params &p, int lane, int targe
     int carry = 0, count = 0, start = 0;
     for (int base = 0; base < p.batch; base += 64) {
         const int i = base + lane;
-        int incl = i < p.batch ? units_of(clamped_len(p, i)) : 0;
+        int incl = i < p.batch ? units_at(p, i) : 0;
 #pragma unroll
         for (int d = 1; d < 64; d <<= 1) {              // inclusive scan across the wavefront
             const int up = __shfl_up(incl, d, 64);
@@ -189,16 +184,6 @@ __device__ __forceinline__ i16x4 read_tr16(const char *lds_addr) {
 
 __device__ __forceinline__ float wave_xor_max(float v, int mask) {
     return fmaxf(v, __shfl_xor(v, mask, 64));
-}
-
-// Workgroups bound to the sequence that owns stream units [seq_first, seq_first + ub): workgroup k
-// is bound iff its share [floor(k U / G), floor((k+1) U / G)) meets that range, which gives
-//   first = ceil((seq_first + 1) G / U) - 1,   last = ceil((seq_first + ub) G / U) - 1.
-__device__ __forceinline__ void bound_workgroups(int seq_first, int ub, int total_units, int active,
-                                                 int &first, int &last) {
-    const long long U = total_units, G = active;
-    first = (int)((((long long)seq_first + 1) * G + U - 1) / U) - 1;
-    last = (int)((((long long)seq_first + ub) * G + U - 1) / U) - 1;
 }
 
 // One 16x16x32 matrix-core step on 16-bit operands held as raw bits; kDtype selects bf16 or fp16.
@@ -272,10 +257,10 @@ __global__ void __launch_bounds__(kThreads, 1) mla_decode_split_kernel(const Par
     int total_units, unused;
     unit_sums(p, l, 0, total_units, unused);
     // never more workgroups than units: every active workgroup then holds at least one unit
-    const int active = total_units < p.num_wg ? total_units : p.num_wg;
+    const int active = mla_plan::active_teams(total_units, p.num_wg);
     if (k >= active) return;                        // uniform over the workgroup
-    const int u_lo = (int)((long long)k * total_units / active);
-    const int u_hi = (int)((long long)(k + 1) * total_units / active);   // > u_lo
+    int u_lo, u_hi;                                 // u_hi > u_lo
+    mla_plan::unit_range(k, total_units, active, u_lo, u_hi);
     int b, seq_first;                               // first sequence of the range, stream index of its first unit
     locate_unit(p, l, u_lo, b, seq_first);
 
@@ -324,15 +309,14 @@ __global__ void __launch_bounds__(kThreads, 1) mla_decode_split_kernel(const Par
     long long row;                    // row of q, out and lse
     auto set_piece = [&](int first_unit) {          // uses b and seq_first
         n = clamped_len(p, b);
-        ub = units_of(n);                                      // > 0
-        const int u_begin = first_unit - seq_first;
-        const int u_end = min(u_hi - seq_first, ub);           // > u_begin
-        t_begin = u_begin * kUnit;
-        t_end = has_token ? min(visible_len(p, n, j), u_end * kUnit) : 0;   // may be <= t_begin: nothing visible here
+        ub = mla_plan::units_of(n, p.unit);                    // > 0
         // the tiles staged cover what the last token of this workgroup sees
-        const int stage_end = kShare > 1 ? min(visible_len(p, n, min(jt * kShare + kShare - 1, p.q_len - 1)), u_end * kUnit) : t_end;
-        n_tiles = stage_end > t_begin ? (stage_end - t_begin + kTile - 1) / kTile : 0;
-        direct = (u_begin == 0 && u_end == ub);                // this team covers the whole sequence
+        const mla_plan::Piece pc = mla_plan::piece_of(n, ub, seq_first, first_unit, u_hi, p.unit, p.q_len, has_token ? j : p.q_len - 1,
+                                                      min(jt * kShare + kShare - 1, p.q_len - 1), has_token);
+        t_begin = pc.t_begin;
+        t_end = pc.t_end;                                      // may be <= t_begin: nothing visible here
+        n_tiles = pc.n_tiles;
+        direct = pc.whole;                                     // this team covers the whole sequence
         kv_b = p.kv + (long long)b * p.kv_batch_bytes;
         row = (long long)b * p.q_len + (has_token ? j : p.q_len - 1);   // a wavefront without a token reads a valid q and writes nothing
     };
@@ -347,12 +331,12 @@ __global__ void __launch_bounds__(kThreads, 1) mla_decode_split_kernel(const Par
     auto issue_loads = [&](int tile) {              // tile of the current piece
         const int tb = t_begin + tile * kTile;
         const int valid_rows = min(n - tb, kTile);                 // >= 1
-        const int last_chunk16 = (valid_rows * (kRowBytes / 16) - 1) * 16;   // byte offset of the last valid chunk
+        const int last_chunk16 = mla_plan::last_chunk_offset(valid_rows);    // byte offset of the last valid chunk
         const char *tile_base = kv_b + (long long)tb * kRowBytes;
 #pragma unroll
         for (int i = 0; i < kTileLoads; ++i) {
-            const int piece = min(i * 1024, last_chunk16);          // scalar
-            st[i] = load_stream16<kTeam>(tile_base + piece, min(lane16, (unsigned)(last_chunk16 - piece)));
+            const int piece = mla_plan::piece_offset(i, last_chunk16);       // scalar
+            st[i] = load_stream16<kTeam>(tile_base + piece, mla_plan::lane_offset(lane16, last_chunk16, piece));
         }
     };
     // ---- a1: Q^T as the MFMA B operand: lane (head r16, k-group g) holds dims 32*kk + 8*g .. +8
@@ -405,15 +389,15 @@ __global__ void __launch_bounds__(kThreads, 1) mla_decode_split_kernel(const Par
         const char *rf_base = nullptr;    // next tile to fetch while tiles are worked on
         int rf_last = 0;                  // byte offset of its last valid 16-byte chunk
         auto refill_piece = [&](int i) {
-            const int piece = min(i * 1024, rf_last);                       // scalar
-            st[i] = load_stream16<kTeam>(rf_base + piece, min(lane16, (unsigned)(rf_last - piece)));
+            const int piece = mla_plan::piece_offset(i, rf_last);           // scalar
+            st[i] = load_stream16<kTeam>(rf_base + piece, mla_plan::lane_offset(lane16, rf_last, piece));
         };
         // The tile to fetch next: this wavefront's next tile of the piece; after its last tile, 36 reads
         // of the sequence's first KB, which cost next to nothing and keep the loop free of a second variant.
         auto set_refill = [&]() {
             const bool fetch = nxt < n_tiles;
             const int ntb = fetch ? t_begin + nxt * kTile : 0;
-            rf_last = fetch ? (min(n - ntb, kTile) * (kRowBytes / 16) - 1) * 16 : 1008;
+            rf_last = fetch ? mla_plan::last_chunk_offset(min(n - ntb, kTile)) : 1008;
             rf_base = kv_b + (long long)ntb * kRowBytes;
         };
         constexpr int kHalfLoads = kTileLoads / 2;     // 18 = 9 with the k-steps + 9 with the value tiles
@@ -677,13 +661,12 @@ __global__ void __launch_bounds__(kThreads, 1) mla_decode_split_kernel(const Par
         // workgroup whose share crosses a sequence boundary does not restart from an empty pipeline
         const bool ep_direct = direct;
         const long long ep_row = row;
-        const long long slot = ((long long)k + b) * p.q_len + j;
+        const long long slot = mla_plan::slot_of(k, b, p.q_len, j);
         const bool more = seq_first + ub < u_hi;
         if (more) {
             const int first_unit = seq_first + ub;
             seq_first = first_unit;
-            ++b;
-            while (units_of(clamped_len(p, b)) == 0) ++b;   // empty sequences hold no units
+            b = mla_plan::next_nonempty(p.seqlens, b + 1, p.max_seqlen, p.unit);   // empty sequences hold no units
             set_piece(first_unit);
             if (w < n_tiles) issue_loads(w);
             load_q();
@@ -799,20 +782,20 @@ __global__ void __launch_bounds__(kCombineCols * kCombineGroups / kCombineSlices
     const bool writes_lse = (slice == 0 && threadIdx.x == 0);
     int total_units, seq_first;
     unit_sums(p, threadIdx.x & 63, b, total_units, seq_first);
-    const int ub = units_of(clamped_len(p, b));
+    const int ub = units_at(p, b);
     float *out = p.out + ((long long)row * kHeads + h) * kDv + col;
     if (ub == 0) {                            // empty sequence
         if (pg == 0) *reinterpret_cast<f32x4 *>(out) = f32x4{0.f, 0.f, 0.f, 0.f};
         if (writes_lse) p.lse[row * kHeads + h] = -INFINITY;
         return;
     }
-    const int active = total_units < p.num_wg ? total_units : p.num_wg;    // as in the main kernel
+    const int active = mla_plan::active_teams(total_units, p.num_wg);       // as in the main kernel
     int k_first, k_last;
-    bound_workgroups(seq_first, ub, total_units, active, k_first, k_last);
+    mla_plan::bound_teams(seq_first, ub, total_units, active, k_first, k_last);
     const int ns = k_last - k_first + 1;
     if (ns == 1) return;                      // the main kernel wrote out / lse directly
     // the pieces of this row sit q_len slots apart
-    const long long first_slot = ((long long)k_first + b) * p.q_len + j;
+    const long long first_slot = mla_plan::slot_of(k_first, b, p.q_len, j);
     const int lstep = p.q_len * kHeads;
     const long long ostep = (long long)p.q_len * kHeads * kDv;
     const float *pl = p.part_lse + first_slot * kHeads + h;
@@ -891,34 +874,45 @@ __global__ void __launch_bounds__(kCombineCols * kCombineGroups / kCombineSlices
     if (writes_lse) p.lse[row * kHeads + h] = tot * 0.6931471805599453f;
 }
 
+// Diagnostic kernel: the partition exactly as the two kernels above derive it (the same device
+// functions on the same arguments), written out as a table of 8 ints per record.  Block x < G writes
+// team x's record {total units, active teams, first unit, end unit, first sequence, that sequence's
+// first unit, 0, 0} (the last four are -1 for an idle team); block G + b writes sequence b's record
+// {total units, first unit, units, first team, last team, 0, 0, 0} (teams -1 for an empty sequence).
+__global__ void __launch_bounds__(64) mla_decode_plan_kernel(const Params p, int *table) {
+    const int l = threadIdx.x;
+    int rec[8] = {0, 0, -1, -1, -1, -1, 0, 0};
+    if ((int)blockIdx.x < p.num_wg) {
+        const int k = blockIdx.x;
+        int total_units, unused;
+        unit_sums(p, l, 0, total_units, unused);
+        const int active = mla_plan::active_teams(total_units, p.num_wg);
+        rec[0] = total_units;
+        rec[1] = active;
+        if (k < active) {
+            mla_plan::unit_range(k, total_units, active, rec[2], rec[3]);
+            locate_unit(p, l, rec[2], rec[4], rec[5]);
+        }
+    } else {
+        const int b = blockIdx.x - p.num_wg;
+        unit_sums(p, l, b, rec[0], rec[1]);
+        rec[2] = units_at(p, b);
+        rec[3] = rec[4] = -1;
+        rec[5] = 0;
+        if (rec[2] > 0)
+            mla_plan::bound_teams(rec[1], rec[2], rec[0], mla_plan::active_teams(rec[0], p.num_wg), rec[3], rec[4]);
+    }
+    if (l < 8) {
+        int v = rec[0];
+#pragma unroll
+        for (int i = 1; i < 8; ++i) v = l == i ? rec[i] : v;
+        table[(long long)blockIdx.x * 8 + l] = v;
+    }
+}
+
 // ---- host side ---------------------------------------------------------------------------------
 
-// Query tokens that one workgroup can take (two wavefronts per token): used when q_len >= 2.
-constexpr int kMaxShare = 2;
-
-// How q_len query tokens are spread: `share` tokens per workgroup, `members` workgroups per team
-// (all members stream the same KV rows), `teams` shares of the unit stream.
-struct Plan {
-    int share, members, teams;
-};
-
-inline Plan plan_for(int q_len, int num_wg, bool direct_orientation) {
-    Plan pl;
-    pl.share = (q_len >= 2 && !direct_orientation) ? 2 : 1;
-    pl.members = (q_len + pl.share - 1) / pl.share;
-    pl.teams = num_wg / pl.members > 0 ? num_wg / pl.members : 1;
-    return pl;
-}
-
-constexpr size_t workspace_bytes_for(int batch, int num_wg) {
-    // One partial slot per (team, sequence, query token) that can occur: (teams + sequences) x q_len.
-    // `batch` counts sequences x tokens.  A team is one or more workgroups and a workgroup takes at
-    // most kMaxShare tokens, so teams x q_len <= kMaxShare x num_wg, or q_len (one team) if larger.
-    const size_t slots = (size_t)kMaxShare * (size_t)num_wg + (size_t)batch + MLA_MAX_Q_LEN;
-    const size_t po = slots * kHeads * kDv * sizeof(float);
-    const size_t pl = slots * kHeads * sizeof(float);
-    return po + ((pl + 15) & ~(size_t)15);
-}
+static_assert(mla_plan::kMaxQLen == MLA_MAX_Q_LEN && mla_plan::kSlotFloats == kHeads * kDv, "plan header and ABI header disagree");
 
 constexpr int kMaxWorkgroups = 1 << 16;
 
@@ -926,12 +920,17 @@ constexpr int kMaxWorkgroups = 1 << 16;
 // on up to MLA_STATIC_MAX_WORKGROUPS compute units and MLA_STATIC_MAX_ROWS (sequence, query token)
 // rows: 19.2 MB that every GPU the library runs on holds until the process ends.  In host code the
 // array's name is only a handle for hipGetSymbolAddress(); kernels get the device address it returns.
-constexpr size_t kStaticBytes = workspace_bytes_for(MLA_STATIC_MAX_ROWS, MLA_STATIC_MAX_WORKGROUPS);
+constexpr size_t kStaticBytes = (2 * MLA_STATIC_MAX_WORKGROUPS + MLA_STATIC_MAX_ROWS + MLA_MAX_Q_LEN) * (size_t)(kHeads * kDv + kHeads) * sizeof(float);
 static __device__ __align__(256) unsigned char scratch[kStaticBytes];
 
 bool misaligned(const void *ptr) { return (reinterpret_cast<uintptr_t>(ptr) & 15u) != 0; }
 
 constexpr int kMaxQLen = MLA_MAX_Q_LEN;
+
+int unit_tokens_for(int flags, int batch, int max_seqlen_kv, int teams) {
+    return (flags & MLA_UNIT_FINE) ? mla_plan::kUnitFine : (flags & MLA_UNIT_COARSE) ? mla_plan::kUnitCoarse
+                                                          : mla_plan::unit_for(batch, max_seqlen_kv, teams);
+}
 
 mla_status_t check_shape(int batch, int num_heads, int max_seqlen_kv) {
     if (batch <= 0 || max_seqlen_kv <= 0 || num_heads <= 0) return MLA_ERR_INVALID_ARG;
@@ -973,9 +972,9 @@ mla_status_t launch(const void *q, const void *kv_cache, int64_t kv_batch_stride
     const bool direct_orientation = (flags & MLA_ORIENT_DIRECT) != 0;
     if (direct_orientation && (q_len > 1 || dtype != MLA_DTYPE_BF16)) return MLA_ERR_UNSUPPORTED_SHAPE;
     // the workspace holds one slot per (team, sequence, query token)
-    const Plan plan = plan_for(q_len, num_wg, direct_orientation);
+    const mla_plan::Spread plan = mla_plan::spread_for(q_len, num_wg, direct_orientation);
     const int teams = plan.teams;
-    if (workspace_bytes < workspace_bytes_for(batch * q_len, num_wg)) return MLA_ERR_WORKSPACE_TOO_SMALL;
+    if (workspace_bytes < mla_plan::workspace_bytes(batch * q_len, num_wg)) return MLA_ERR_WORKSPACE_TOO_SMALL;
 
     // the main kernel needs more dynamic LDS than the default limit: raise it once per device
     static std::mutex mu;
@@ -1015,6 +1014,7 @@ mla_status_t launch(const void *q, const void *kv_cache, int64_t kv_batch_stride
     p.q_len = q_len;
     p.max_seqlen = max_seqlen_kv;
     p.num_wg = teams;
+    p.unit = unit_tokens_for(flags, batch, max_seqlen_kv, teams);
     p.scale_log2e = scale * 1.4426950408889634f;
 
     hipStream_t hs = static_cast<hipStream_t>(stream);
@@ -1052,9 +1052,7 @@ static mla_status_t planned_workgroups(int batch, int q_len, int max_seqlen_kv, 
     if (hipGetDevice(&dev) != hipSuccess) return MLA_ERR_HIP;
     if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0)
         return MLA_ERR_HIP;
-    const long long units_max = (long long)batch * ((max_seqlen_kv + kUnit - 1) / kUnit);
-    const int n = (q_len > 1 || units_max <= 8ll * cus) ? cus : cus * 13 / 16;
-    *num_wg = n < 1 ? 1 : n;
+    *num_wg = mla_plan::workgroups_for(batch, q_len, max_seqlen_kv, cus);
     if (num_wg_max) *num_wg_max = cus;
     return MLA_OK;
 }
@@ -1070,7 +1068,7 @@ mla_status_t mla_decode_workspace_size(int batch, int num_heads, int max_seqlen_
         st = planned_workgroups(batch, 1, max_seqlen_kv, &num_workgroups, &size_for);
         if (st != MLA_OK) return st;
     }
-    *bytes = workspace_bytes_for(batch, size_for);
+    *bytes = mla_plan::workspace_bytes(batch, size_for);
     if (num_workgroups_used) *num_workgroups_used = num_workgroups;
     return MLA_OK;
 }
@@ -1088,7 +1086,8 @@ mla_status_t mla_decode_typed(const void *q, const void *kv_cache, int64_t kv_ba
                                max_seqlen_kv, scale, out, lse, workspace);
     if (st != MLA_OK) return st;
     if (num_workgroups < 0 || num_workgroups > kMaxWorkgroups) return MLA_ERR_INVALID_ARG;
-    if ((flags & ~(MLA_PHASE_SPLIT | MLA_PHASE_COMBINE | MLA_ORIENT_DIRECT)) != 0) return MLA_ERR_INVALID_ARG;
+    if ((flags & ~(MLA_PHASE_SPLIT | MLA_PHASE_COMBINE | MLA_ORIENT_DIRECT | MLA_UNIT_FINE | MLA_UNIT_COARSE)) != 0) return MLA_ERR_INVALID_ARG;
+    if ((flags & MLA_UNIT_FINE) && (flags & MLA_UNIT_COARSE)) return MLA_ERR_INVALID_ARG;
     if ((flags & (MLA_PHASE_SPLIT | MLA_PHASE_COMBINE)) == 0) return MLA_ERR_INVALID_ARG;
     if (num_workgroups == 0) {
         st = planned_workgroups(batch, q_len, max_seqlen_kv, &num_workgroups, nullptr);
@@ -1146,6 +1145,38 @@ mla_status_t mla_decode_static(const void *q, const void *kv_cache, int64_t kv_b
     if (batch * q_len > MLA_STATIC_MAX_ROWS || num_wg > MLA_STATIC_MAX_WORKGROUPS) return MLA_ERR_STATIC_LIMIT;
     return launch(q, kv_cache, kv_batch_stride, cache_seqlens, batch, q_len, max_seqlen_kv, scale, out, lse,
                   ws, kStaticBytes, num_wg, MLA_PHASE_SPLIT | MLA_PHASE_COMBINE, dtype, stream);
+}
+
+mla_status_t mla_decode_plan_table(const int32_t *cache_seqlens, int batch, int q_len, int max_seqlen_kv,
+                                   int num_workgroups, int flags, int32_t *table, int *teams, int *unit_tokens,
+                                   void *stream) {
+    if (!cache_seqlens || !table || !teams || !unit_tokens) return MLA_ERR_INVALID_ARG;
+    if ((reinterpret_cast<uintptr_t>(cache_seqlens) & 3u) || (reinterpret_cast<uintptr_t>(table) & 3u)) return MLA_ERR_INVALID_ARG;
+    if (q_len < 1 || q_len > kMaxQLen) return MLA_ERR_UNSUPPORTED_SHAPE;
+    mla_status_t st = check_shape(batch, kHeads, max_seqlen_kv);
+    if (st != MLA_OK) return st;
+    if (num_workgroups < 0 || num_workgroups > kMaxWorkgroups) return MLA_ERR_INVALID_ARG;
+    if ((flags & ~(MLA_ORIENT_DIRECT | MLA_UNIT_FINE | MLA_UNIT_COARSE)) != 0) return MLA_ERR_INVALID_ARG;
+    if ((flags & MLA_UNIT_FINE) && (flags & MLA_UNIT_COARSE)) return MLA_ERR_INVALID_ARG;
+    if (num_workgroups == 0) {
+        st = planned_workgroups(batch, q_len, max_seqlen_kv, &num_workgroups, nullptr);
+        if (st != MLA_OK) return st;
+    }
+    const mla_plan::Spread plan = mla_plan::spread_for(q_len, num_workgroups, (flags & MLA_ORIENT_DIRECT) != 0);
+    Params p = {};
+    p.seqlens = cache_seqlens;
+    p.batch = batch;
+    p.q_len = q_len;
+    p.max_seqlen = max_seqlen_kv;
+    p.num_wg = plan.teams;
+    p.unit = unit_tokens_for(flags, batch, max_seqlen_kv, plan.teams);
+    *teams = plan.teams;
+    *unit_tokens = p.unit;
+    void *args[] = {&p, &table};
+    if (hipLaunchKernel(reinterpret_cast<const void *>(mla_decode_plan_kernel), dim3(plan.teams + batch), dim3(64), args, 0,
+                        static_cast<hipStream_t>(stream)) != hipSuccess)
+        return MLA_ERR_HIP;
+    return MLA_OK;
 }
 
 mla_status_t mla_decode_planned_workgroups(int batch, int q_len, int max_seqlen_kv, int *num_workgroups) {

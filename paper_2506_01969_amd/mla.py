@@ -57,6 +57,8 @@ def lib():
         L.mla_decode_typed.restype = ci
         L.mla_decode_static.argtypes = [vp, vp, ctypes.c_int64, vp, ci, ci, ci, ci, ci, ctypes.c_float, vp, vp, vp]
         L.mla_decode_static.restype = ci
+        L.mla_decode_plan_table.argtypes = [vp, ci, ci, ci, ci, ci, vp, cip, cip, vp]
+        L.mla_decode_plan_table.restype = ci
         L.mla_decode_planned_workgroups.argtypes = [ci, ci, ci, cip]
         L.mla_decode_planned_workgroups.restype = ci
         L.mla_status_string.argtypes = [ci]
@@ -104,6 +106,8 @@ def _check_tensors(q, kv_cache, cache_seqlens):
 PHASE_SPLIT = 1
 PHASE_COMBINE = 2
 ORIENT_DIRECT = 8
+UNIT_FINE = 16
+UNIT_COARSE = 32
 DTYPE_BF16 = 0
 DTYPE_F16 = 1
 
@@ -172,3 +176,21 @@ def mla_decode_static(q, kv_cache, cache_seqlens, scale, out, lse):
     if st != MLA_OK:
         raise MlaError(st, "mla_decode_static")
     return out, lse
+
+
+def mla_decode_plan_table(cache_seqlens, q_len, max_seqlen_kv, num_workgroups=0, flags=0):
+    """``mla_decode_plan_table`` of the C ABI -> (table [teams + batch, 8] int32 on the device, teams,
+    unit_tokens): the partition as the kernels derive it on the device (tests, diagnosis)."""
+    if cache_seqlens.dtype != torch.int32 or not cache_seqlens.is_cuda or not cache_seqlens.is_contiguous():
+        raise TypeError("cache_seqlens must be a contiguous int32 device tensor")
+    batch = cache_seqlens.numel()
+    rows = int(num_workgroups) or mla_decode_planned_workgroups(batch, q_len, max_seqlen_kv)
+    table = torch.full((rows + batch, 8), -7, dtype=torch.int32, device=cache_seqlens.device)
+    teams, unit = ctypes.c_int(0), ctypes.c_int(0)
+    stream = ctypes.c_void_p(torch.cuda.current_stream(cache_seqlens.device).cuda_stream)
+    st = lib().mla_decode_plan_table(ctypes.c_void_p(cache_seqlens.data_ptr()), batch, q_len, max_seqlen_kv,
+                                     int(num_workgroups), int(flags), ctypes.c_void_p(table.data_ptr()),
+                                     ctypes.byref(teams), ctypes.byref(unit), stream)
+    if st != MLA_OK:
+        raise MlaError(st, "mla_decode_plan_table")
+    return table[:teams.value + batch], teams.value, unit.value

@@ -494,3 +494,60 @@ def test_direct_orientation_benchmark_configs(oracle, cfg):
     print("case direct config", cfg, "oracle", flush=True)
     ref_o, ref_l = _oracle(oracle, q, kv, l)
     _check(out, lse, ref_o, ref_l, label="direct config %d" % cfg)
+
+
+# ---- the partition as the kernels derive it on the device, against its plain definition ---------------
+
+def test_device_plan_equals_its_definition():
+    """`mla_decode_plan_table` runs the kernels' own device functions (wavefront-wide sums and scans over
+    the lengths, the range, locate and bound rules).  Here the same table is built from the definition
+    with numpy prefix sums and a brute-force search over the teams' ranges."""
+    dev = _dev()
+    rng = np.random.default_rng(77)
+    for case in range(120):
+        batch = int(rng.integers(1, 40)) if case % 4 else int(rng.integers(65, 300))
+        max_len = int(rng.choice([1, 33, 130, 700, 4096, 70000]))
+        lens = rng.integers(-3, max_len + 50, size=batch)
+        lens[rng.random(batch) < 0.15] = 0
+        if case % 9 == 0:
+            lens[:] = 0
+        q_len = int(rng.choice([1, 1, 2, 3, 5, 8]))
+        num_wg = int(rng.choice([1, 2, 7, 64, 208, 256, 999]))
+        flags = [0, mla.UNIT_FINE, mla.UNIT_COARSE][case % 3]
+        print("plan case %d: batch %d max_len %d q_len %d num_wg %d flags %d" % (case, batch, max_len, q_len, num_wg, flags), flush=True)
+        ld = torch.tensor(lens, dtype=torch.int32, device=dev)
+        table, teams, unit = mla.mla_decode_plan_table(ld, q_len, max_len, num_wg, flags)
+        torch.cuda.synchronize()
+        table = table.cpu().numpy()
+        share = 2 if q_len >= 2 else 1
+        members = -(-q_len // share)
+        assert teams == max(1, num_wg // members)
+        if flags == mla.UNIT_FINE:
+            assert unit == 32
+        elif flags == mla.UNIT_COARSE:
+            assert unit == 128
+        else:
+            assert unit == (32 if batch * -(-max_len // 128) < teams else 128)
+        units = -(-np.clip(lens, 0, max_len) // unit)
+        ends = np.cumsum(units)
+        firsts = ends - units
+        total = int(ends[-1])
+        active = min(total, teams)
+        ranges = [(k * total // active, (k + 1) * total // active) for k in range(active)]
+        for k in range(teams):
+            rec = table[k]
+            assert rec[0] == total and rec[1] == active
+            if k >= active:
+                assert (rec[2:6] == -1).all()
+                continue
+            lo, hi = ranges[k]
+            b = int(np.searchsorted(ends, lo, side="right"))
+            assert (rec[2], rec[3], rec[4], rec[5]) == (lo, hi, b, firsts[b]), (k, rec)
+        for b in range(batch):
+            rec = table[teams + b]
+            assert (rec[0], rec[1], rec[2]) == (total, firsts[b], units[b]), (b, rec)
+            if units[b] == 0:
+                assert rec[3] == -1 and rec[4] == -1
+                continue
+            meets = [k for k, (lo, hi) in enumerate(ranges) if lo < ends[b] and hi > firsts[b]]
+            assert (rec[3], rec[4]) == (meets[0], meets[-1]) and meets == list(range(meets[0], meets[-1] + 1)), (b, rec)
