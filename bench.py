@@ -25,6 +25,10 @@ TRAFFIC_FILE = os.path.join(ROOT, "profiles", "mla_decode_split_b16_kv64k_traffi
 CPU_SAMPLE_SEQS = 16            # sequences of the batch the oracle is timed on (about 15 s of CPU work)
 
 
+def unit_flag(mla, args):
+    return {"auto": 0, "fine": mla.UNIT_FINE, "coarse": mla.UNIT_COARSE}[args.unit]
+
+
 def sweep(torch, inputs, mla, dev, args):
     """Whole-call time over the grid of the paper's Figure 1 (Section 4.1: batch 16 and 32, KV length
     512 ... 64K, one query token, 16 heads).  Values are drawn on the device (timing only; parity over
@@ -45,9 +49,11 @@ def sweep(torch, inputs, mla, dev, args):
             out = torch.empty((batch, 1, 16, 512), dtype=torch.float32, device=dev)
             lse = torch.empty((batch, 16), dtype=torch.float32, device=dev)
 
+            phases = None if args.unit == "auto" else (mla.PHASE_SPLIT | mla.PHASE_COMBINE | unit_flag(mla, args))
+
             def step(i):
                 mla.mla_decode(q, kvs[i % n_buf], lens, inputs.SCALE, out=out, lse=lse, workspace=ws,
-                               num_workgroups=args.workgroups or None)
+                               num_workgroups=args.workgroups or None, phases=phases)
             for i in range(args.warmup):
                 step(i)
             torch.cuda.synchronize()
@@ -79,6 +85,9 @@ def main():
                     help="query tokens per sequence (1 = the headline metric; the paper names 1 or 2)")
     ap.add_argument("--dtype", choices=("bf16", "fp16"), default="bf16",
                     help="element type of q and the KV cache (bf16 = the headline metric; fp16 = the paper's own)")
+    ap.add_argument("--unit", choices=("auto", "fine", "coarse"), default="auto",
+                    help="rows per unit of the KV stream: auto = the library's rule (128, or 32 for a short stream), "
+                         "fine = 32, coarse = 128 (comparison)")
     ap.add_argument("--sweep", action="store_true",
                     help="time the whole call over batch 16 and 32 x KV length 512 ... 64K (the grid of the "
                          "paper's Figure 1) and print one JSON line per point instead of the benchmark line")
@@ -141,7 +150,7 @@ def main():
     alg_bytes += (args.q_len - 1) * batch * (16 * 576 * 2 + 16 * 512 * 4 + 16 * 4)
     alg_flops *= args.q_len
 
-    orient = mla.ORIENT_DIRECT if args.orientation == "direct" else 0
+    orient = (mla.ORIENT_DIRECT if args.orientation == "direct" else 0) | unit_flag(mla, args)
 
     def step(i, phases=mla.PHASE_SPLIT | mla.PHASE_COMBINE):
         mla.mla_decode(qd, kvs[i % n_buf], ld, inputs.SCALE, out=out, lse=lse, workspace=ws,

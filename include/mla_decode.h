@@ -122,8 +122,8 @@ mla_status_t mla_decode(const void *q, const void *kv_cache, int64_t kv_batch_st
  *                   MLA_UNIT_FINE / MLA_UNIT_COARSE (at most one) force the unit of the stream to
  *                   MLA_UNIT_TOKENS_FINE / MLA_UNIT_TOKENS rows.  Without either the unit is 128
  *                   rows (one 32-row tile for each of a workgroup's four wavefronts) unless
- *                   batch * ceil(max_seqlen_kv / 128) is below the number of workgroups: such a short
- *                   stream is divided by the tile, so that it spreads over more compute units.
+ *                   4 * batch * ceil(max_seqlen_kv / 32) is at most the number of workgroups: so tiny a
+ *                   batch is divided by the tile, so that it spreads over more compute units.
  * All other arguments, and all error behaviour, are those of mla_decode().
  */
 #define MLA_UNIT_TOKENS 128
@@ -192,7 +192,8 @@ mla_status_t mla_decode_planned_workgroups(int batch, int q_len, int max_seqlen_
  * record into `table` (device, (num_workgroups + batch) * 8 int32 or more; with num_workgroups == 0,
  * size it with mla_decode_planned_workgroups()):
  *   record k < *teams        {total units, active teams, first unit, end unit, first sequence, that
- *                             sequence's first unit, 0, 0} of team k (the middle four -1 if idle)
+ *                             sequence's first unit, its clamped length, 0} of team k (first unit ..
+ *                             the sequence's first unit are -1, the length 0, for an idle team)
  *   record *teams + b        {total units, first unit, units, first team, last team, 0, 0, 0} of
  *                             sequence b (teams -1 for an empty sequence)
  * *teams (host) receives the number of teams (workgroups per query-token pair) the unit stream is

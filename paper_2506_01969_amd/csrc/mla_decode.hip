@@ -83,7 +83,8 @@ static_assert(kLdsBytes <= 160 * 1024, "LDS of one compute unit");
 static_assert(kWaves * kTile == MLA_UNIT_TOKENS && mla_plan::kUnitCoarse == MLA_UNIT_TOKENS && mla_plan::kUnitFine == MLA_UNIT_TOKENS_FINE,
               "header and kernel disagree on the scheduling units");
 constexpr int kCombineCols = 128;               // threads that cover the 512 value columns, 4 each
-constexpr int kCombineWide = 4;                 // groups of such threads per block when a sequence has many pieces
+constexpr int kCombineWide = 4;                 // groups of such threads per block when a sequence has many pieces,
+constexpr int kCombineWidest = 16;              // and when it has more than 64 (one or two sequences over all compute units)
 constexpr int kSchedMfma = 0x008;              // instruction classes of sched_group_barrier
 constexpr int kSchedDsRead = 0x100;
 constexpr int kSchedVmemRead = 0x020;
@@ -112,6 +113,7 @@ struct Params {
     int max_seqlen;
     int num_wg;               // G: teams (one workgroup per two query tokens) the unit stream is divided over
     int unit;                 // KV rows per unit of the stream: 128, or 32 for a short stream
+    int stream_out;           // nonzero: the epilogue's stores are marked non-temporal (short streams, see launch())
     float scale_log2e;        // scale * log2(e): scores are kept in the base-2 domain
 };
 
@@ -121,49 +123,70 @@ __device__ __forceinline__ int clamped_len(const Params &p, int b) { return mla_
 
 __device__ __forceinline__ int units_at(const Params &p, int b) { return mla_plan::units_of(clamped_len(p, b), p.unit); }
 
-__device__ __forceinline__ int wave_sum(int v) {
-#pragma unroll
-    for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, 64);
+// Inclusive prefix sum over the 64 lanes of a wavefront with data-parallel primitives: row shifts by
+// 1, 2, 4, 8 inside each row of 16 lanes, then the last lane of row 0 (2) added to all of row 1 (3),
+// then lane 31 added to rows 2 and 3.  A lane without a source keeps 0 as its addend.  Ten vector
+// instructions and no trip through the LDS crossbar, which the shuffle builtins would take six times.
+__device__ __forceinline__ int wave_scan(int v) {
+    v += __builtin_amdgcn_update_dpp(0, v, 0x111, 0xf, 0xf, false);   // row_shr:1
+    v += __builtin_amdgcn_update_dpp(0, v, 0x112, 0xf, 0xf, false);   // row_shr:2
+    v += __builtin_amdgcn_update_dpp(0, v, 0x114, 0xf, 0xf, false);   // row_shr:4
+    v += __builtin_amdgcn_update_dpp(0, v, 0x118, 0xf, 0xf, false);   // row_shr:8
+    v += __builtin_amdgcn_update_dpp(0, v, 0x142, 0xa, 0xf, false);   // row_bcast:15 into rows 1 and 3
+    v += __builtin_amdgcn_update_dpp(0, v, 0x143, 0xc, 0xf, false);   // row_bcast:31 into rows 2 and 3
     return v;
 }
 
-// Units of all sequences (total) and of the sequences before b, one sequence per lane and 64 at
-// a time, so the lengths are fetched with one vector load instead of a chain of dependent scalar
-// loads.  Every wavefront computes this for itself; the results are wave-uniform.
-__device__ __forceinline__ void unit_sums(const Params &p, int lane, int b, int &total, int &before_b) {
-    int tot = 0, bef = 0;
-    for (int base = 0; base < p.batch; base += 64) {
-        const int i = base + lane;
-        const int u = i < p.batch ? units_at(p, i) : 0;
-        tot += u;
-        bef += i < b ? u : 0;
-    }
-    total = __builtin_amdgcn_readfirstlane(wave_sum(tot));
-    before_b = __builtin_amdgcn_readfirstlane(wave_sum(bef));
+// Sequences base .. base + 63, one per lane: the clamped length and the number of units of the
+// sequences up to and including the lane's (carry = units of the sequences before base).  The
+// lengths are fetched with one vector load instead of a chain of dependent scalar loads.
+struct LaneScan {
+    int len, incl;
+};
+__device__ __forceinline__ LaneScan scan_lengths(const Params &p, int lane, int base, int carry) {
+    const int i = base + lane;
+    LaneScan s;
+    s.len = i < p.batch ? clamped_len(p, i) : 0;
+    s.incl = wave_scan(mla_plan::units_of(s.len, p.unit)) + carry;
+    return s;
 }
 
-// The sequence that holds unit `target` of the stream (0 <= target < total units) and the stream
-// index of that sequence's first unit: b = number of sequences whose inclusive prefix is <= target.
-__device__ __forceinline__ void locate_unit(const Params &p, int lane, int target, int &b, int &first) {
-    int carry = 0, count = 0, start = 0;
+// Units of all sequences (total) and of the sequences before b.  Every wavefront computes this for
+// itself; the results are wave-uniform.
+__device__ __forceinline__ void unit_sums(const Params &p, int lane, int b, int &total, int &before_b) {
+    int carry = 0, bef = 0;
     for (int base = 0; base < p.batch; base += 64) {
-        const int i = base + lane;
-        int incl = i < p.batch ? units_at(p, i) : 0;
-#pragma unroll
-        for (int d = 1; d < 64; d <<= 1) {              // inclusive scan across the wavefront
-            const int up = __shfl_up(incl, d, 64);
-            if (lane >= d) incl += up;
-        }
-        incl += carry;
-        const unsigned long long below = __builtin_amdgcn_ballot_w64(i < p.batch && incl <= target);
-        if (below != 0) {
-            count += __builtin_popcountll(below);
-            start = __builtin_amdgcn_readlane(incl, 63 - __builtin_clzll(below));
-        }
-        carry = __builtin_amdgcn_readlane(incl, 63);
+        const LaneScan s = scan_lengths(p, lane, base, carry);
+        if (b == base) bef = carry;
+        else if (b > base && b < base + 64) bef = __builtin_amdgcn_readlane(s.incl, b - base - 1);
+        carry = __builtin_amdgcn_readlane(s.incl, 63);
     }
-    b = count;
-    first = start;
+    total = carry;
+    before_b = bef;
+}
+
+// The sequence that holds unit `target` of the stream (0 <= target < total units), the stream index
+// of that sequence's first unit and its length, from the scan of one chunk of 64 sequences; returns
+// false if the unit lies beyond the chunk.  b = number of sequences whose inclusive prefix is <= target.
+__device__ __forceinline__ bool locate_in_chunk(const Params &p, const LaneScan &s, int lane, int base, int carry, int target,
+                                                int &b, int &first, int &n) {
+    if (__builtin_amdgcn_readlane(s.incl, 63) <= target) return false;
+    const unsigned long long below = __builtin_amdgcn_ballot_w64(base + lane < p.batch && s.incl <= target);
+    const int in_chunk = __builtin_popcountll(below);          // the lanes below form a prefix: the scan never decreases
+    b = base + in_chunk;
+    first = in_chunk ? __builtin_amdgcn_readlane(s.incl, in_chunk - 1) : carry;
+    n = __builtin_amdgcn_readlane(s.len, in_chunk);
+    return true;
+}
+
+__device__ __forceinline__ void locate_unit(const Params &p, int lane, int target, int &b, int &first, int &n) {
+    int carry = 0;
+    b = first = n = 0;
+    for (int base = 0; base < p.batch; base += 64) {
+        const LaneScan s = scan_lengths(p, lane, base, carry);
+        if (locate_in_chunk(p, s, lane, base, carry, target, b, first, n)) return;
+        carry = __builtin_amdgcn_readlane(s.incl, 63);
+    }
 }
 
 // 16-byte streaming load at (wave-uniform base) + (32-bit lane offset): the uniform part stays in
@@ -254,15 +277,21 @@ __global__ void __launch_bounds__(kThreads, 1) mla_decode_split_kernel(const Par
     const int tk = w & (kShare - 1);                     // this wavefront's query token within the workgroup
     const int j = jt * kShare + tk;                      // query token of this wavefront (scalar)
     const bool has_token = j < p.q_len;                  // odd q_len: the last wavefront pair has one token only
+    // Up to 64 sequences (one per lane): one vector load of the lengths and one scan give the total,
+    // this team's range, its first sequence and that sequence's length.  Larger batches take a
+    // second pass over the lengths once the total is known.
     int total_units, unused;
-    unit_sums(p, l, 0, total_units, unused);
+    const LaneScan first_chunk = scan_lengths(p, l, 0, 0);
+    if (p.batch <= 64) total_units = __builtin_amdgcn_readlane(first_chunk.incl, 63);
+    else unit_sums(p, l, 0, total_units, unused);
     // never more workgroups than units: every active workgroup then holds at least one unit
     const int active = mla_plan::active_teams(total_units, p.num_wg);
     if (k >= active) return;                        // uniform over the workgroup
     int u_lo, u_hi;                                 // u_hi > u_lo
     mla_plan::unit_range(k, total_units, active, u_lo, u_hi);
-    int b, seq_first;                               // first sequence of the range, stream index of its first unit
-    locate_unit(p, l, u_lo, b, seq_first);
+    int b, seq_first, n_first;                      // first sequence of the range, stream index of its first unit, its length
+    if (p.batch <= 64) locate_in_chunk(p, first_chunk, l, 0, 0, u_lo, b, seq_first, n_first);
+    else locate_unit(p, l, u_lo, b, seq_first, n_first);
 
     char *my = smem + w * kWaveLds;                       // private tile of this wavefront
     // LDS addresses (bytes) of the three access patterns
@@ -307,8 +336,8 @@ __global__ void __launch_bounds__(kThreads, 1) mla_decode_split_kernel(const Par
     bool direct;
     const char *kv_b;
     long long row;                    // row of q, out and lse
-    auto set_piece = [&](int first_unit) {          // uses b and seq_first
-        n = clamped_len(p, b);
+    auto set_piece = [&](int first_unit, int n_b) {   // uses b and seq_first; n_b: length of sequence b
+        n = n_b;
         ub = mla_plan::units_of(n, p.unit);                    // > 0
         // the tiles staged cover what the last token of this workgroup sees
         const mla_plan::Piece pc = mla_plan::piece_of(n, ub, seq_first, first_unit, u_hi, p.unit, p.q_len, has_token ? j : p.q_len - 1,
@@ -349,7 +378,7 @@ __global__ void __launch_bounds__(kThreads, 1) mla_decode_split_kernel(const Par
 
     // The first tile is requested before q: loads come back in order, the tile is needed first (for
     // the LDS write) and q only after it (for the first product), so q's trip overlaps that write.
-    set_piece(u_lo);
+    set_piece(u_lo, n_first);
     if (w < n_tiles) issue_loads(w);
     load_q();
     while (true) {
@@ -667,7 +696,7 @@ __global__ void __launch_bounds__(kThreads, 1) mla_decode_split_kernel(const Par
             const int first_unit = seq_first + ub;
             seq_first = first_unit;
             b = mla_plan::next_nonempty(p.seqlens, b + 1, p.max_seqlen, p.unit);   // empty sequences hold no units
-            set_piece(first_unit);
+            set_piece(first_unit, clamped_len(p, b));
             if (w < n_tiles) issue_loads(w);
             load_q();
         }
@@ -744,7 +773,11 @@ __global__ void __launch_bounds__(kThreads, 1) mla_decode_split_kernel(const Par
 #pragma unroll
                 for (int i = 0; i < 4; ++i) dst[(4 * g + i) * kDv + ct * 16 + r16] = acc[i];
             } else {                      // head r16, columns 16 ct + 4g .. +3; equation (4): transpose by addressing
-                if (has_token) *reinterpret_cast<f32x4 *>(dst + r16 * kDv + ct * 16 + g * 4) = acc;
+                f32x4 *to = reinterpret_cast<f32x4 *>(dst + r16 * kDv + ct * 16 + g * 4);
+                if (has_token) {
+                    if (p.stream_out) __builtin_nontemporal_store(acc, to);
+                    else *to = acc;
+                }
             }
         }
         if (w < kShare && has_token && (kDirect ? r16 == 0 : g == 0)) {
@@ -877,7 +910,7 @@ __global__ void __launch_bounds__(kCombineCols * kCombineGroups / kCombineSlices
 // Diagnostic kernel: the partition exactly as the two kernels above derive it (the same device
 // functions on the same arguments), written out as a table of 8 ints per record.  Block x < G writes
 // team x's record {total units, active teams, first unit, end unit, first sequence, that sequence's
-// first unit, 0, 0} (the last four are -1 for an idle team); block G + b writes sequence b's record
+// first unit, its clamped length, 0} (first unit .. first unit of the sequence are -1 for an idle team); block G + b writes sequence b's record
 // {total units, first unit, units, first team, last team, 0, 0, 0} (teams -1 for an empty sequence).
 __global__ void __launch_bounds__(64) mla_decode_plan_kernel(const Params p, int *table) {
     const int l = threadIdx.x;
@@ -891,7 +924,12 @@ __global__ void __launch_bounds__(64) mla_decode_plan_kernel(const Params p, int
         rec[1] = active;
         if (k < active) {
             mla_plan::unit_range(k, total_units, active, rec[2], rec[3]);
-            locate_unit(p, l, rec[2], rec[4], rec[5]);
+            if (p.batch <= 64) {                       // the same two routes as the split kernel
+                const LaneScan s = scan_lengths(p, l, 0, 0);
+                locate_in_chunk(p, s, l, 0, 0, rec[2], rec[4], rec[5], rec[6]);
+            } else {
+                locate_unit(p, l, rec[2], rec[4], rec[5], rec[6]);
+            }
         }
     } else {
         const int b = blockIdx.x - p.num_wg;
@@ -1015,6 +1053,13 @@ mla_status_t launch(const void *q, const void *kv_cache, int64_t kv_batch_stride
     p.max_seqlen = max_seqlen_kv;
     p.num_wg = teams;
     p.unit = unit_tokens_for(flags, batch, max_seqlen_kv, teams);
+    // With a short stream all workgroups finish within a few microseconds of each other and their
+    // partial results (32 KB each) are still dirty in the L2 caches when the kernel ends; the merge
+    // kernel then starts only after they have been written back (4 us for 256 of them, against 2 us
+    // when the workgroups finish apart).  Marked non-temporal, the stores leave for memory as they
+    // are issued: batch 16, KV 512 ... 4096: 1.0 us less per call; batch 32, KV 4096: 1.5 us less.
+    // With a long stream the same marking costs 1 us (batch 16, KV 16K and 64K), so it is not used there.
+    p.stream_out = (long long)batch * ((max_seqlen_kv + mla_plan::kUnitCoarse - 1) / mla_plan::kUnitCoarse) <= 4ll * teams;
     p.scale_log2e = scale * 1.4426950408889634f;
 
     hipStream_t hs = static_cast<hipStream_t>(stream);
@@ -1025,9 +1070,14 @@ mla_status_t launch(const void *q, const void *kv_cache, int64_t kv_batch_stride
     }
     if (flags & MLA_PHASE_COMBINE) {
         // pieces per sequence: about teams / batch, plus the two at its ends
-        const bool wide = teams / batch + 2 > 16;
-        const kernel_fn combine_fn = wide ? mla_decode_combine_kernel<kCombineWide, kCombineWide> : mla_decode_combine_kernel<1, 1>;
-        if (launch_kernel(reinterpret_cast<const void *>(combine_fn), batch * q_len * kHeads * (wide ? kCombineWide : 1), kCombineCols, 0, hs, p) != hipSuccess)
+        const int pieces = teams / batch + 2;
+        // batch 1 or 2 on 256 workgroups (258 / 130 pieces): 16 groups x 16 slices, 4.5 us less per call at batch 1
+        // than 4 x 4; batch 4 (66 pieces) is 0.5 us faster with 4 x 4
+        const int width = pieces > 100 ? kCombineWidest : pieces > 16 ? kCombineWide : 1;
+        const kernel_fn combine_fn = width == kCombineWidest ? mla_decode_combine_kernel<kCombineWidest, kCombineWidest>
+                                     : width == kCombineWide ? mla_decode_combine_kernel<kCombineWide, kCombineWide>
+                                                             : mla_decode_combine_kernel<1, 1>;
+        if (launch_kernel(reinterpret_cast<const void *>(combine_fn), batch * q_len * kHeads * width, kCombineCols, 0, hs, p) != hipSuccess)
             return MLA_ERR_HIP;
     }
     return MLA_OK;

@@ -52,9 +52,13 @@ MLA_PLAN_FN int visible_len(int n, int q_len, int j) {
 // Never more teams than units: every active team then holds at least one unit.
 MLA_PLAN_FN int active_teams(int total_units, int teams) { return total_units < teams ? total_units : teams; }
 
+// Range [floor(k U / A), floor((k + 1) U / A)) of team k < A, A <= 65536, in 32-bit arithmetic: with
+// U = q A + r, floor(k U / A) = k q + floor(k r / A), and k r < A^2 fits an unsigned int.  (A 64-bit
+// division costs the kernel's start several hundred nanoseconds.)
 MLA_PLAN_FN void unit_range(int k, int total_units, int active, int &lo, int &hi) {
-    lo = (int)((long long)k * total_units / active);
-    hi = (int)((long long)(k + 1) * total_units / active);
+    const unsigned A = (unsigned)active, q = (unsigned)total_units / A, r = (unsigned)total_units % A;
+    lo = (int)((unsigned)k * q + (unsigned)k * r / A);
+    hi = (int)((unsigned)(k + 1) * q + (unsigned)(k + 1) * r / A);
 }
 
 // Teams bound to the sequence that owns stream units [seq_first, seq_first + ub), ub > 0: team k is
@@ -160,12 +164,14 @@ MLA_PLAN_FN size_t workspace_bytes(int rows, int num_wg) {
     return po + ((pl + 15) & ~(size_t)15);
 }
 
-// The unit: 128 rows (one tile for each wavefront of a workgroup) unless the batch cannot even hold
-// one such unit per workgroup; then 32 rows, so that a short stream spreads over more compute units
-// and each of them takes in less before its first product.
+// The unit: 128 rows (one tile for each wavefront of a workgroup), or 32 rows (one tile) for a tiny
+// batch: one whose tiles number at most a quarter of the workgroups.  Such a batch then spreads over
+// four times as many compute units, each of which takes in a quarter as much before its first product
+// (batch 1, KV 512 and 1024: 1.7 us less per call).  Beyond that size the finer unit only multiplies
+// the partial results to merge (batch 1, KV 8192: 4.7 us more per call with 256 tiles than with 64 units).
 MLA_PLAN_FN int unit_for(int batch, int max_seqlen, int num_wg) {
-    const long long coarse = (long long)batch * ((max_seqlen + kUnitCoarse - 1) / kUnitCoarse);
-    return coarse < num_wg ? kUnitFine : kUnitCoarse;
+    const long long tiles = (long long)batch * ((max_seqlen + kUnitFine - 1) / kUnitFine);
+    return 4 * tiles <= num_wg ? kUnitFine : kUnitCoarse;
 }
 
 // Workgroups of the automatic plan on a device of `cus` compute units: 13 of every 16 for one query

@@ -97,6 +97,7 @@ static void run_case(int case_id, int batch, int max_seqlen, const std::vector<i
         int u_lo, u_hi;
         unit_range(k, U, A, u_lo, u_hi);
         CHECK(u_lo == prev_hi && u_hi > u_lo && u_hi <= U);
+        CHECK(u_lo == (int)((long long)k * U / A) && u_hi == (int)((long long)(k + 1) * U / A));   // the 32-bit form is exact
         prev_hi = u_hi;
         int b, seq_first;
         locate_unit_serial(lens, batch, max_seqlen, unit, u_lo, b, seq_first);
@@ -205,9 +206,10 @@ int main() {
     bad += workgroups_for(16, 1, 4096, 256) != 256;
     bad += workgroups_for(16, 2, 65536, 256) != 256;
     bad += workgroups_for(1, 1, 1, 1) != 1;
-    bad += unit_for(1, 512, 256) != kUnitFine;          // 4 coarse units for 256 workgroups
-    bad += unit_for(16, 1024, 256) != kUnitFine;        // 128 coarse units
-    bad += unit_for(16, 2048, 256) != kUnitCoarse;      // 256 coarse units: one per workgroup
+    bad += unit_for(1, 512, 256) != kUnitFine;          // 16 tiles for 256 workgroups
+    bad += unit_for(1, 2048, 256) != kUnitFine;         // 64 tiles
+    bad += unit_for(1, 2049, 256) != kUnitCoarse;
+    bad += unit_for(16, 512, 256) != kUnitCoarse;       // 256 tiles
     bad += unit_for(16, 65536, 208) != kUnitCoarse;
     if (bad) {
         std::printf("FAILED automatic plan / unit rule (%d)\n", bad);

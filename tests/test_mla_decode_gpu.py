@@ -527,7 +527,7 @@ def test_device_plan_equals_its_definition():
         elif flags == mla.UNIT_COARSE:
             assert unit == 128
         else:
-            assert unit == (32 if batch * -(-max_len // 128) < teams else 128)
+            assert unit == (32 if 4 * batch * -(-max_len // 32) <= teams else 128)
         units = -(-np.clip(lens, 0, max_len) // unit)
         ends = np.cumsum(units)
         firsts = ends - units
@@ -542,7 +542,7 @@ def test_device_plan_equals_its_definition():
                 continue
             lo, hi = ranges[k]
             b = int(np.searchsorted(ends, lo, side="right"))
-            assert (rec[2], rec[3], rec[4], rec[5]) == (lo, hi, b, firsts[b]), (k, rec)
+            assert (rec[2], rec[3], rec[4], rec[5], rec[6]) == (lo, hi, b, firsts[b], min(max(int(lens[b]), 0), max_len)), (k, rec)
         for b in range(batch):
             rec = table[teams + b]
             assert (rec[0], rec[1], rec[2]) == (total, firsts[b], units[b]), (b, rec)
