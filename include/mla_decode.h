@@ -47,6 +47,7 @@ typedef enum {
 
 /* Fixed problem shape (DeepSeek-R1 share of one GPU, Section 4.1). */
 #define MLA_NUM_HEADS 16
+#define MLA_MAX_ABS_SCALE 1.0e6f
 #define MLA_D_QK 576
 #define MLA_D_V 512
 
@@ -87,7 +88,10 @@ mla_status_t mla_decode_workspace_size(int batch, int num_heads, int max_seqlen_
  *                   on the device; rows at or beyond a sequence's length are never
  *                   read into the result
  *   batch, num_heads, max_seqlen_kv   as above
- *   scale           multiplies q.k before the softmax (1/sqrt(192) for DeepSeek-R1)
+ *   scale           multiplies q.k before the softmax (1/sqrt(192) for DeepSeek-R1); finite and
+ *                   |scale| <= MLA_MAX_ABS_SCALE, else MLA_ERR_INVALID_ARG.  The scaled scores are
+ *                   held in fp32 and must stay finite there (they do for inputs below 1e14 in
+ *                   magnitude); scores that overflow give NaN results
  *   out             device, fp32 [batch][1][16][512], contiguous, 16-byte aligned
  *   lse             device, fp32 [batch][16]: natural log of sum_t exp(scale * q.k_t)
  *   workspace       device, 16-byte aligned, >= mla_decode_workspace_size(.., 0, ..) bytes;

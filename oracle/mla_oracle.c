@@ -157,7 +157,11 @@ int mla_oracle_decode_general(const uint16_t *q, const uint16_t *kv, int64_t kv_
         int n = seqlens[b] - (q_len - 1 - j);      /* causal among the new tokens */
         if (n < 0) n = 0;
         double *scratch = (double *)malloc(sizeof(double) * (size_t)(n > 0 ? n : 1));
-        if (!scratch) { fail = 1; continue; }
+        if (!scratch) {
+#pragma omp atomic write
+            fail = 1;
+            continue;
+        }
         attend_range_t(q + (size_t)r * d_qk, kv + (size_t)b * kv_batch_stride, d_qk, d_v, 0, n,
                        scale, out + (size_t)r * d_v, lse + r, scratch, dtype);
         free(scratch);
@@ -191,7 +195,11 @@ int mla_oracle_decode(const uint16_t *q, const uint16_t *kv, int64_t kv_batch_st
         int b = p / heads, h = p % heads;
         int n = seqlens[b];
         double *scratch = (double *)malloc(sizeof(double) * (size_t)(n > 0 ? n : 1));
-        if (!scratch) { fail = 1; continue; }
+        if (!scratch) {
+#pragma omp atomic write
+            fail = 1;
+            continue;
+        }
         attend_range(q + ((size_t)b * heads + h) * d_qk, kv + (size_t)b * kv_batch_stride,
                      d_qk, d_v, 0, n, scale, out + ((size_t)b * heads + h) * d_v,
                      lse + (size_t)b * heads + h, scratch);

@@ -989,7 +989,9 @@ mla_status_t validate(const void *q, const void *kv_cache, int64_t kv_batch_stri
         (reinterpret_cast<uintptr_t>(lse) & 3u) || (reinterpret_cast<uintptr_t>(cache_seqlens) & 3u))
         return MLA_ERR_INVALID_ARG;
     if (kv_batch_stride < (int64_t)max_seqlen_kv * kDqk || (kv_batch_stride & 7) != 0) return MLA_ERR_INVALID_ARG;
-    if (!(scale == scale) || std::isinf(scale)) return MLA_ERR_INVALID_ARG;
+    // scores are kept in fp32: with |scale| <= MLA_MAX_ABS_SCALE they stay finite for any inputs of magnitude
+    // below 1e14, so every tile has a finite maximum and the softmax never forms inf - inf
+    if (!(std::fabs(scale) <= MLA_MAX_ABS_SCALE)) return MLA_ERR_INVALID_ARG;      // also rejects NaN
     return MLA_OK;
 }
 

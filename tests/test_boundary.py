@@ -93,6 +93,7 @@ def test_decode_argument_errors_come_before_any_device_work():
     assert _call(stride=4096 * 576 + 4) == E.MLA_ERR_INVALID_ARG  # breaks 16-byte alignment of rows
     assert _call(scale=float("nan")) == E.MLA_ERR_INVALID_ARG
     assert _call(scale=float("inf")) == E.MLA_ERR_INVALID_ARG
+    assert _call(scale=2.0e6) == E.MLA_ERR_INVALID_ARG and _call(scale=-2.0e6) == E.MLA_ERR_INVALID_ARG    # beyond MLA_MAX_ABS_SCALE
     assert _call(num_wg=-1) == E.MLA_ERR_INVALID_ARG
     assert _call(num_wg=1 << 20) == E.MLA_ERR_INVALID_ARG
     assert _call(phases=0) == E.MLA_ERR_INVALID_ARG

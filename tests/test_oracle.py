@@ -85,6 +85,25 @@ def test_probabilities_sum_to_one(oracle):
             assert abs(math.fsum(p.tolist()) - 1.0) < 1e-12
 
 
+def test_probabilities_by_value(oracle):
+    """Each probability against exp(s_t - lse) with the scores and the log-sum-exp from numpy in float64 on
+    independently decoded inputs (bf16 bits << 16 reinterpreted as float32): a dropped, squared or misplaced
+    scale, a wrong head or a shifted row in the probability routine changes the values, not their sum."""
+    qb, kvb, lens = _small(2, 300, 4, 32, seed=6, seqlens=[300, 123])
+    dec = lambda bits: (bits.astype(np.uint32) << 16).view(np.float32).astype(np.float64)
+    qf, kvf = dec(qb), dec(kvb)
+    scale = 0.21
+    for b in range(2):
+        for h in range(4):
+            s = scale * (kvf[b, :lens[b]] @ qf[b].reshape(4, 32)[h])
+            want = np.exp(s - (s.max() + np.log(np.exp(s - s.max()).sum())))
+            got = oracle.probs(qb, kvb, lens, scale, b, h)
+            np.testing.assert_allclose(got, want, rtol=1e-12, atol=1e-15)
+            # and the probabilities reproduce the oracle's own output when applied to V by numpy
+            out, _ = oracle.decode(qb, kvb, lens, scale, 20)
+            np.testing.assert_allclose(out[b, h], got @ kvf[b, :lens[b], :20], rtol=0, atol=1e-13)
+
+
 # ---- 3. constant K / zero q -----------------------------------------------------------------
 
 def test_constant_k_returns_that_row(oracle):
