@@ -74,6 +74,84 @@ def unit_flag(mla, args):
     return {"auto": 0, "fine": mla.UNIT_FINE, "coarse": mla.UNIT_COARSE}[args.unit]
 
 
+def timeline(torch, inputs, dev, args):
+    """Where the time of one call goes, from the measurement build of the library (the product source compiled
+    with -DMLA_TIMELINE: every wavefront of the main kernel and every block of the merge kernel record the
+    100 MHz real-time counter at their phase boundaries).  Prints one JSON line: for each phase the minimum,
+    median and maximum over the wavefronts (blocks), in microseconds after the first wavefront's start, as
+    medians over `--steps` calls (each preceded by warm calls on rotated KV buffers)."""
+    import ctypes
+    import statistics
+    from paper_2506_01969_amd import build as hip_build
+    if not os.path.exists(hip_build.TIMELINE_LIB_PATH):
+        hip_build.build_timeline()
+    L = ctypes.CDLL(hip_build.TIMELINE_LIB_PATH)
+    vp, ci = ctypes.c_void_p, ctypes.c_int
+    L.mla_decode.argtypes = [vp, vp, ctypes.c_int64, vp, ci, ci, ci, ctypes.c_float, vp, vp, vp, ctypes.c_size_t, vp]
+    L.mla_decode.restype = ci
+    L.mla_decode_workspace_size.argtypes = [ci, ci, ci, ci, ctypes.POINTER(ctypes.c_size_t), ctypes.POINTER(ci)]
+    L.mla_timeline_buffer.argtypes = [vp]
+    cfg = inputs.CONFIGS[args.config]
+    q, kv, lens = inputs.make_config(args.config)
+    batch, max_seqlen = cfg["batch"], cfg["seqlen"]
+    qd, ld = q.to(dev), lens.to(dev)
+    n_buf = max(2, min(16, -(-(512 << 20) // (kv.numel() * 2))))
+    kvs = [kv.to(dev)]
+    for _ in range(n_buf - 1):
+        kvs.append(kvs[0].clone())
+    need, nwg = ctypes.c_size_t(0), ci(0)
+    assert L.mla_decode_workspace_size(batch, 16, max_seqlen, 0, ctypes.byref(need), ctypes.byref(nwg)) == 0
+    ws = torch.empty((need.value,), dtype=torch.uint8, device=dev)
+    out = torch.empty((batch, 1, 16, 512), dtype=torch.float32, device=dev)
+    lse = torch.empty((batch, 16), dtype=torch.float32, device=dev)
+    blocks = batch * 16 * 16                                    # the widest merge launch
+    stamps = torch.zeros(((1 << 20) + blocks * 4,), dtype=torch.int64, device=dev)
+    stream = vp(torch.cuda.current_stream(dev).cuda_stream)
+
+    def call(i):
+        st = L.mla_decode(vp(qd.data_ptr()), vp(kvs[i % n_buf].data_ptr()), kvs[0].stride(0), vp(ld.data_ptr()), batch, 16,
+                          max_seqlen, inputs.SCALE, vp(out.data_ptr()), vp(lse.data_ptr()), vp(ws.data_ptr()), need.value, stream)
+        assert st == 0, st
+    names = ["start", "lengths_summed", "first_piece_known", "first_loads_issued", "first_tile_in_lds", "last_tile_done",
+             "accumulators_in_lds", "results_stored"]
+    cnames = ["start", "lengths_summed", "merged", "stored"]
+    rows = {("split", n): [] for n in names}
+    rows.update({("combine", n): [] for n in cnames})
+    gaps = []
+    for rep_ in range(args.steps):
+        L.mla_timeline_buffer(None)
+        for i in range(max(args.warmup, 3)):
+            call(rep_ + i)
+        stamps.zero_()
+        torch.cuda.synchronize()
+        L.mla_timeline_buffer(vp(stamps.data_ptr()))
+        call(rep_)
+        torch.cuda.synchronize()
+        host = stamps.cpu()
+        sp = host[:nwg.value * 4 * 8].view(-1, 8)
+        sp = sp[sp[:, 0] != 0].double() / 100.0                   # 100 MHz -> microseconds
+        cb = host[(1 << 20):].view(-1, 4)
+        cb = cb[cb[:, 0] != 0].double() / 100.0
+        t0 = float(sp[:, 0].min())
+        for i, n in enumerate(names):
+            col = sp[:, i][sp[:, i] != 0] - t0
+            if col.numel():
+                rows[("split", n)].append((float(col.min()), float(col.median()), float(col.max())))
+        for i, n in enumerate(cnames):
+            if cb.shape[0]:
+                col = cb[:, i] - t0
+                rows[("combine", n)].append((float(col.min()), float(col.median()), float(col.max())))
+        if cb.shape[0]:
+            gaps.append(float(cb[:, 0].min()) - float(sp[:, 7].max()))
+    L.mla_timeline_buffer(None)
+    med = lambda v: [round(statistics.median(x[j] for x in v), 2) for j in range(3)] if v else None
+    print(json.dumps({"timeline_us_after_first_wavefront_start": "min / median / max over wavefronts (blocks), medians of %d calls" % args.steps,
+                      "config": args.config, "batch": batch, "max_seqlen": max_seqlen, "workgroups": nwg.value,
+                      "main_kernel": {n: med(rows[("split", n)]) for n in names},
+                      "merge_kernel": {n: med(rows[("combine", n)]) for n in cnames},
+                      "gap_main_end_to_merge_start_us": round(statistics.median(gaps), 2) if gaps else None}))
+
+
 def sweep(torch, inputs, mla, dev, args):
     """Whole-call time over the grid of the paper's Figure 1 (Section 4.1: batch 16 and 32, KV length
     512 ... 64K, one query token, 16 heads).  Values are drawn on the device (timing only; parity over
@@ -138,6 +216,9 @@ def main():
                          "paper's Figure 1) and print one JSON line per point instead of the benchmark line")
     ap.add_argument("--batches", default="16,32", help="batch sizes of --sweep")
     ap.add_argument("--kv-lens", default="512,1024,2048,4096,8192,16384,32768,65536", help="KV lengths of --sweep")
+    ap.add_argument("--timeline", action="store_true",
+                    help="per-phase time stamps of one call of --config from the measurement build of the library "
+                         "(medians over --steps calls), as one JSON line; then exit")
     ap.add_argument("--ceiling-probe", action="store_true",
                     help="only run the plain streaming-read probe (no arithmetic, the main kernel's request pattern) over "
                          "the KV buffers of --config for several numbers of workgroups, print one JSON line each and exit")
@@ -172,6 +253,10 @@ def main():
 
     if args.sweep:
         sweep(torch, inputs, mla, dev, args)
+        return
+
+    if args.timeline:
+        timeline(torch, inputs, dev, args)
         return
 
     cfg = inputs.CONFIGS[args.config]

@@ -9,6 +9,8 @@ ROOT = os.path.dirname(_HERE)
 SOURCES = [os.path.join(_HERE, "csrc", "mla_decode.hip")]
 LIB_PATH = os.path.join(_HERE, "libmla_decode.so")
 # measurement only (the streaming-read ceiling the benchmark reports): its own library, no part of the product
+# measurement only: the product source with time stamps at its phase boundaries (bench.py --timeline)
+TIMELINE_LIB_PATH = os.path.join(_HERE, "libmla_decode_timeline.so")
 PROBE_SOURCES = [os.path.join(_HERE, "csrc", "hbm_probe.hip")]
 PROBE_LIB_PATH = os.path.join(_HERE, "libhbm_probe.so")
 
@@ -20,10 +22,10 @@ HIPCC_FLAGS = [
 ]
 
 
-def _compile(sources, lib_path, verbose):
+def _compile(sources, lib_path, verbose, extra=()):
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
     tmp = lib_path + ".tmp.%d" % os.getpid()
-    cmd = [hipcc] + HIPCC_FLAGS + sources + ["-o", tmp]
+    cmd = [hipcc] + HIPCC_FLAGS + list(extra) + sources + ["-o", tmp]
     res = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
     out = "\n".join(line for line in res.stdout.splitlines() if "packed-fp32-ops" not in line)
     if res.returncode != 0:
@@ -39,6 +41,11 @@ def build_library(verbose: bool = False) -> str:
     return _compile(SOURCES, LIB_PATH, verbose)
 
 
+def build_timeline(verbose: bool = False) -> str:
+    """The product source compiled with -DMLA_TIMELINE (measurement only).  Returns the library path."""
+    return _compile(SOURCES, TIMELINE_LIB_PATH, verbose, extra=["-DMLA_TIMELINE"])
+
+
 def build_probe(verbose: bool = False) -> str:
     """The streaming-read probe of the benchmark (measurement only).  Returns the library path."""
     return _compile(PROBE_SOURCES, PROBE_LIB_PATH, verbose)
@@ -47,3 +54,4 @@ def build_probe(verbose: bool = False) -> str:
 if __name__ == "__main__":
     print(build_library(verbose=True))
     print(build_probe(verbose=True))
+    print(build_timeline(verbose=True))

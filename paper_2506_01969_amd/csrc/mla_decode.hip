@@ -115,7 +115,22 @@ struct Params {
     int unit;                 // KV rows per unit of the stream: 128, or 32 for a short stream
     int stream_out;           // nonzero: the epilogue's stores are marked non-temporal (short streams, see launch())
     float scale_log2e;        // scale * log2(e): scores are kept in the base-2 domain
+    long long *timeline;      // measurement build only (MLA_TIMELINE), else null: where the kernels leave their time stamps
 };
+
+// Measurement build (-DMLA_TIMELINE, a library of its own that the benchmark's --timeline mode loads):
+// every wavefront of the main kernel and the first thread of every merge block record the 100 MHz
+// real-time counter at the phase boundaries marked MLA_STAMP below (the first time each is passed) and
+// write them to Params::timeline when they finish.  In the product build the marks compile to nothing.
+#ifdef MLA_TIMELINE
+#define MLA_STAMPS(n) long long stamps[n] = {}
+#define MLA_STAMP(i) do { if (stamps[i] == 0) stamps[i] = (long long)__builtin_amdgcn_s_memrealtime(); } while (0)
+constexpr int kSplitStamps = 8, kCombineStamps = 4;
+constexpr long long kCombineStampBase = 1 << 20;      // in stamps, after the main kernel's
+#else
+#define MLA_STAMPS(n) ((void)0)
+#define MLA_STAMP(i) ((void)0)
+#endif
 
 // The integer rules of the partition (units, ranges, slots, tile offsets) live in mla_plan.h, shared
 // with the host code and the CPU tests; below are only their wave-parallel evaluations.
@@ -257,6 +272,8 @@ __global__ void __launch_bounds__(kThreads, 1) mla_decode_split_kernel(const Par
     constexpr int kGroups = kWaves / kShare;      // wavefronts that work for the same query token
     extern __shared__ __attribute__((aligned(16))) char smem[];
 
+    MLA_STAMPS(8);
+    MLA_STAMP(0);                 // wavefront started
     const int tid = threadIdx.x;
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6);   // wavefront in workgroup (scalar)
     const int l = tid & 63;       // lane
@@ -284,6 +301,7 @@ __global__ void __launch_bounds__(kThreads, 1) mla_decode_split_kernel(const Par
     const LaneScan first_chunk = scan_lengths(p, l, 0, 0);
     if (p.batch <= 64) total_units = __builtin_amdgcn_readlane(first_chunk.incl, 63);
     else unit_sums(p, l, 0, total_units, unused);
+    MLA_STAMP(1);                 // lengths read and summed
     // never more workgroups than units: every active workgroup then holds at least one unit
     const int active = mla_plan::active_teams(total_units, p.num_wg);
     if (k >= active) return;                        // uniform over the workgroup
@@ -379,8 +397,10 @@ __global__ void __launch_bounds__(kThreads, 1) mla_decode_split_kernel(const Par
     // The first tile is requested before q: loads come back in order, the tile is needed first (for
     // the LDS write) and q only after it (for the first product), so q's trip overlaps that write.
     set_piece(u_lo, n_first);
+    MLA_STAMP(2);                 // range located, first piece known
     if (w < n_tiles) issue_loads(w);
     load_q();
+    MLA_STAMP(3);                 // first tile and q requested (the wavefront waits here while the memory path is full)
     while (true) {
         // this wavefront's tiles of the piece: w, w + 4, w + 8, ...; the first tile and q are on their way
         int cur = w, nxt = w + kWaves;
@@ -644,6 +664,7 @@ __global__ void __launch_bounds__(kThreads, 1) mla_decode_split_kernel(const Par
                 set_refill();
                 write_tile();
                 if (cur == w) wait_for_q();
+                MLA_STAMP(4);     // first tile arrived and written to LDS, q arrived
                 process_tile(std::integral_constant<int, 3>{}, my + k_off, my + v_off, t_begin + cur * kTile);
                 cur = nxt;
                 nxt += kWaves;
@@ -686,6 +707,7 @@ __global__ void __launch_bounds__(kThreads, 1) mla_decode_split_kernel(const Par
             }
         }
 
+        MLA_STAMP(5);             // last tile of the (first) piece done
         // ---- the next piece's q and first tile go in flight before this piece's epilogue, so a
         // workgroup whose share crosses a sequence boundary does not restart from an empty pipeline
         const bool ep_direct = direct;
@@ -727,6 +749,7 @@ __global__ void __launch_bounds__(kThreads, 1) mla_decode_split_kernel(const Par
 #pragma unroll
         for (int ct = 0; ct < kDvTiles; ++ct) *reinterpret_cast<f32x4 *>(my + ct * 1024 + l * 16) = o[ct];
         __syncthreads();
+        MLA_STAMP(6);             // all four wavefronts have put their accumulators in LDS
 
         // Statistics of the head(s) whose accumulator elements this lane holds: head r16 in all four
         // elements (transposed orientation), or heads 4g .. 4g+3, one per element (direct orientation).
@@ -789,6 +812,14 @@ __global__ void __launch_bounds__(kThreads, 1) mla_decode_split_kernel(const Par
             }
         }
 
+#ifdef MLA_TIMELINE
+        if (!more && p.timeline) {
+            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");      // the results have left
+            MLA_STAMP(7);
+            if (l == 0)
+                for (int i = 0; i < kSplitStamps; ++i) p.timeline[((long long)blockIdx.x * kWaves + w) * kSplitStamps + i] = stamps[i];
+        }
+#endif
         if (!more) break;
         __syncthreads();              // the tiles are overwritten next; everyone must be done reading them
     }
@@ -803,6 +834,8 @@ __global__ void __launch_bounds__(kThreads, 1) mla_decode_split_kernel(const Par
 template <int kCombineGroups, int kCombineSlices>
 __global__ void __launch_bounds__(kCombineCols * kCombineGroups / kCombineSlices) mla_decode_combine_kernel(const Params p) {
     constexpr int kGroupThreads = kCombineCols / kCombineSlices;   // threads of a group, 4 columns each
+    MLA_STAMPS(4);
+    MLA_STAMP(0);                 // block started
     const int rh = blockIdx.x / kCombineSlices;
     const int slice = blockIdx.x - rh * kCombineSlices;
     const int row = rh / kHeads;              // (sequence, query token)
@@ -815,6 +848,7 @@ __global__ void __launch_bounds__(kCombineCols * kCombineGroups / kCombineSlices
     const bool writes_lse = (slice == 0 && threadIdx.x == 0);
     int total_units, seq_first;
     unit_sums(p, threadIdx.x & 63, b, total_units, seq_first);
+    MLA_STAMP(1);                 // lengths read and summed
     const int ub = units_at(p, b);
     float *out = p.out + ((long long)row * kHeads + h) * kDv + col;
     if (ub == 0) {                            // empty sequence
@@ -903,7 +937,16 @@ __global__ void __launch_bounds__(kCombineCols * kCombineGroups / kCombineSlices
     }
     const float tot = m + __builtin_amdgcn_logf(sum);
     acc *= 1.0f / sum;
+    MLA_STAMP(2);                 // partial results arrived and merged
     *reinterpret_cast<f32x4 *>(out) = acc;
+#ifdef MLA_TIMELINE
+    if (p.timeline) {
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        MLA_STAMP(3);             // result stored
+        if (threadIdx.x == 0)
+            for (int i = 0; i < kCombineStamps; ++i) p.timeline[kCombineStampBase + (long long)blockIdx.x * kCombineStamps + i] = stamps[i];
+    }
+#endif
     if (writes_lse) p.lse[row * kHeads + h] = tot * 0.6931471805599453f;
 }
 
@@ -1003,6 +1046,8 @@ hipError_t launch_kernel(const void *fn, int blocks, int threads, size_t lds_byt
     return hipLaunchKernel(fn, dim3(blocks), dim3(threads), args, lds_bytes, stream);
 }
 
+long long *timeline_buffer = nullptr;      // set only through mla_timeline_buffer() of the measurement build
+
 // Everything below runs only after validate() passed.
 mla_status_t launch(const void *q, const void *kv_cache, int64_t kv_batch_stride,
                     const int32_t *cache_seqlens, int batch, int q_len, int max_seqlen_kv, float scale,
@@ -1063,6 +1108,7 @@ mla_status_t launch(const void *q, const void *kv_cache, int64_t kv_batch_stride
     // With a long stream the same marking costs 1 us (batch 16, KV 16K and 64K), so it is not used there.
     p.stream_out = (long long)batch * ((max_seqlen_kv + mla_plan::kUnitCoarse - 1) / mla_plan::kUnitCoarse) <= 4ll * teams;
     p.scale_log2e = scale * 1.4426950408889634f;
+    p.timeline = timeline_buffer;
 
     hipStream_t hs = static_cast<hipStream_t>(stream);
     if (flags & MLA_PHASE_SPLIT) {
@@ -1236,6 +1282,12 @@ mla_status_t mla_decode_planned_workgroups(int batch, int q_len, int max_seqlen_
     if (q_len < 1 || q_len > kMaxQLen) return MLA_ERR_UNSUPPORTED_SHAPE;
     return planned_workgroups(batch, q_len, max_seqlen_kv, num_workgroups, nullptr);
 }
+
+#ifdef MLA_TIMELINE
+// Measurement build only: where the kernels of later calls leave their time stamps (device memory of
+// at least 8 MB + 32 bytes per merge block, zeroed by the caller), or NULL to switch them off.
+void mla_timeline_buffer(void *device_buffer) { timeline_buffer = static_cast<long long *>(device_buffer); }
+#endif
 
 const char *mla_status_string(mla_status_t status) {
     switch (status) {
