@@ -65,11 +65,12 @@ constexpr int kHeads = MLA_NUM_HEADS;        // 16
 constexpr int kDqk = MLA_D_QK;               // 576
 constexpr int kDv = MLA_D_V;                 // 512
 constexpr int kRowBytes = kDqk * 2;          // 1152 bytes per KV row
-constexpr int kLdsRow = kRowBytes + 16;      // LDS row stride: +16 B so 16 rows hit 64 distinct banks
+constexpr int kLdsPad = 32;                  // bytes between the rows of a tile in LDS
+constexpr int kLdsRow = kRowBytes + kLdsPad; // LDS row stride 1184 B = 32 mod 64: see the access patterns in the main kernel
 constexpr int kTile = 32;                    // tokens per wavefront step (MFMA K of the PV product)
 constexpr int kWaves = 4;                    // wavefronts per workgroup
 constexpr int kThreads = kWaves * 64;
-constexpr int kWaveLds = kTile * kLdsRow;    // 37,376 B private tile per wavefront
+constexpr int kWaveLds = kTile * kLdsRow;    // 37,888 B private tile per wavefront
 constexpr int kTileLoads = kTile * kRowBytes / 1024;   // 36 loads of 64 lanes x 16 B per tile
 static_assert(kTileLoads * 1024 == kTile * kRowBytes, "a tile must be a whole number of 1 KB pieces");
 static_assert(kRowBytes == mla_plan::kRowBytes && kTile == mla_plan::kTileRows && kTileLoads == mla_plan::kTileLoads,
@@ -314,35 +315,38 @@ __global__ void __launch_bounds__(kThreads, 1) mla_decode_split_kernel(const Par
     char *my = smem + w * kWaveLds;                       // private tile of this wavefront
     // LDS addresses (bytes) of the three access patterns
     // write side: piece i, lane l holds chunk 64 i + l; lanes at or past the row boundary inside
-    // the piece (lane 72 (q+1) - 64 i, a function of i mod 9) skip the 16-byte row padding
+    // the piece (lane 72 (q+1) - 64 i, a function of i mod 9) skip the row padding
     char *wr_flat[9];
 #pragma unroll
     for (int r = 0; r < 9; ++r) {
         const int boundary = 72 * ((r * 64) / 72 + 1) - r * 64;     // 72, 8, 16, ..., 56, 64
-        wr_flat[r] = my + l * 16 + (l >= boundary ? 16 : 0);
+        wr_flat[r] = my + l * 16 + (l >= boundary ? kLdsPad : 0);
     }
-    // MFMA position r (0..15) of a score block is not token r of the block's 16 tokens but a permuted
-    // one.  The order of the tokens inside a tile is free (both products sum over them); the one
-    // chosen lets each transposing V / V^T read below, whose first 32 lanes touch eight LDS rows, fall
-    // on rows of one parity: the row stride is 292 words, so every second row starts 72 = 64 + 8
-    // banks on and eight such rows of 8 words tile the 64 banks exactly.  With the identity order
-    // rows overlap in their banks and every such read takes two passes or more.
-    //   transposed: position r holds token rho(r) = 2 r mod 16 + (r >= 8): positions 0..7 (the rows
-    //               of k-groups 0 and 1) are the even tokens, 8..15 the odd ones
-    //   direct:     position t holds token tau(t) = 2 (t mod 4) + 8 (t / 8) + (t / 4 mod 2): the first
-    //               halves 8g .. 8g+3 of the k-groups are even tokens, the second halves the odd ones
-    const int k_row = kDirect ? 2 * (r16 & 3) + (r16 & 8) + ((r16 >> 2) & 1) : ((2 * r16) & 15) + (r16 >> 3);
+    // Bank behaviour of the three LDS access patterns, measured one pattern at a time with a probe kernel
+    // and the SQ_LDS_BANK_CONFLICT counter (64 banks of 4 bytes, 256 bytes per cycle):
+    //   K operand, ds_read_b128: lane (r16, g) reads 16 bytes of row r16 at chunk 4 kk + g.  A cycle serves
+    //     lanes 0..7 of one 16-lane group together with lanes 8..15 of another, so rows 0..7 must fall on
+    //     eight distinct 16-byte bank groups that, shifted by the other group's 16 g, miss those of rows
+    //     8..15.  A row stride of 32 mod 64 bytes does that (rows r and r + 8 share a bank group, the four
+    //     groups alternate between the even and the odd ones): every stride of 16 or 48 mod 64, such as
+    //     1152 + 16, costs each of these reads a second pass, whatever the order of the rows.
+    //   V^T operand, ds_read_b64_tr_b16: a cycle serves 32 lanes = eight rows x 32 bytes; with this stride
+    //     rows 4g + q (q = the lane's quad) of k-groups g = 0, 1 and of g = 2, 3 tile the 64 banks exactly.
+    //   tile write, ds_write_b128: conflict-free for every position of the row boundary inside a load.
+    // So token t of a 16-token score block simply sits on MFMA position t in the transposed orientation.
+    // The direct orientation reads rows by token position 8g .. 8g+3 and 8g+4 .. 8g+7 (its P operand is
+    // transposed across lanes), and position t holds token tau(t) = t xor 4 (t / 8): the first read of
+    // k-groups 0, 1 then takes rows 0..3 and 12..15, the second rows 4..7 and 8..11, eight rows that differ mod 8.
+    const int k_row = kDirect ? (r16 ^ ((r16 & 8) >> 1)) : r16;
     const int k_off = k_row * kLdsRow + g * 16;           // K operand: token k_row (+16), chunk 4*kk + g
     // V^T operand through the transposing read: within each 16-lane group, lane j points at
     // row j/4, columns 4*(j%4)..+3 of a 4x16 block and receives column j, rows 0..3.
     // Tokens of the two reads, in the order of the other operand's 8 k-values: transposed
-    // orientation rho(4g) .. rho(4g+3) and 16 more; direct orientation tau(8g) .. tau(8g+3) (in the
-    // second half of the tile for g >= 2) and the next row each, tau(t + 4) = tau(t) + 1
-    // token of score-block row 4g + i (this lane's elements i = 0..3): rho(4g + i) = tok0 + 2 i
-    const int tok0 = 8 * (g & 1) + (g >> 1);
-    const int v_row = kDirect ? 16 * (g >> 1) + 8 * (g & 1) + 2 * (r16 >> 2) : tok0 + 2 * (r16 >> 2);
+    // orientation 4g .. 4g+3 and 16 more; direct orientation tau(8g) .. tau(8g+3) (in the second half
+    // of the tile for g >= 2) and tau(8g+4) .. tau(8g+7), four rows further on (g even) or back (g odd)
+    const int v_row = kDirect ? 16 * (g >> 1) + 12 * (g & 1) + (r16 >> 2) : 4 * g + (r16 >> 2);
     const int v_off = v_row * kLdsRow + (r16 & 3) * 8;
-    constexpr int kVSecond = (kDirect ? 1 : 16) * kLdsRow;
+    const int v_second = kDirect ? ((g & 1) ? -4 : 4) * kLdsRow : 16 * kLdsRow;
     // direct orientation: P crosses lanes as fp32 [16 heads][32 tokens], in the rescale path's slot
     float *p_tr = reinterpret_cast<float *>(smem + kRescaleOff + w * 2048);
     float *stat_m = reinterpret_cast<float *>(smem + kStatsOff);
@@ -433,7 +437,7 @@ __global__ void __launch_bounds__(kThreads, 1) mla_decode_split_kernel(const Par
         auto write_tile = [&]() {
 #pragma unroll
             for (int i = 0; i < kTileLoads; ++i)
-                *reinterpret_cast<u32x4 *>(wr_flat[i % 9] + i * 1024 + ((i * 64) / 72) * 16) = st[i];
+                *reinterpret_cast<u32x4 *>(wr_flat[i % 9] + i * 1024 + ((i * 64) / 72) * kLdsPad) = st[i];
         };
         const char *rf_base = nullptr;    // next tile to fetch while tiles are worked on
         int rf_last = 0;                  // byte offset of its last valid 16-byte chunk
@@ -556,14 +560,14 @@ __global__ void __launch_bounds__(kThreads, 1) mla_decode_split_kernel(const Par
                     pr[4 + i] = hi4[i];
                 }
             } else {
-            // this lane now holds, for head r16, tokens tb + tok0 + 2i (s0[i]) and 16 more (s1[i])
+            // this lane now holds, for head r16, tokens tb + 4g + i (s0[i]) and 16 more (s1[i])
 
             // ---- a4: scale (base-2 domain) and mask the tail ------------------------------
             float x[8];
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
-                x[i] = (tb + tok0 + 2 * i < t_end) ? s0[i] * p.scale_log2e : -INFINITY;
-                x[4 + i] = (tb + 16 + tok0 + 2 * i < t_end) ? s1[i] * p.scale_log2e : -INFINITY;
+                x[i] = (tb + 4 * g + i < t_end) ? s0[i] * p.scale_log2e : -INFINITY;
+                x[4 + i] = (tb + 16 + 4 * g + i < t_end) ? s1[i] * p.scale_log2e : -INFINITY;
             }
 
             // ---- a5: online softmax (Algorithm 1: m, l update) -----------------------------
@@ -618,10 +622,11 @@ __global__ void __launch_bounds__(kThreads, 1) mla_decode_split_kernel(const Par
             // The transposing reads run kVAhead value tiles ahead of their MFMAs.
             {
                 i16x4 vb[kVAhead][2];
+                const char *rd_v2 = rd_v + v_second;      // the tile's other 16 rows (direct orientation: 4 rows on or back)
 #pragma unroll
                 for (int ct = 0; ct < kVAhead; ++ct) {
                     vb[ct][0] = read_tr16(rd_v + ct * 32);
-                    vb[ct][1] = read_tr16(rd_v + kVSecond + ct * 32);
+                    vb[ct][1] = read_tr16(rd_v2 + ct * 32);
                 }
 #pragma unroll
                 for (int ct = 0; ct < kDvTiles; ++ct) {
@@ -630,7 +635,7 @@ __global__ void __launch_bounds__(kThreads, 1) mla_decode_split_kernel(const Par
                     __builtin_memcpy(&vt, vv, 16);
                     if (ct + kVAhead < kDvTiles) {
                         vb[ct % kVAhead][0] = read_tr16(rd_v + (ct + kVAhead) * 32);
-                        vb[ct % kVAhead][1] = read_tr16(rd_v + kVSecond + (ct + kVAhead) * 32);
+                        vb[ct % kVAhead][1] = read_tr16(rd_v2 + (ct + kVAhead) * 32);
                     }
                     if constexpr (kDirect) {
                         o[ct] = mfma_16x16x32<kDtype>(p_hi, vt, o[ct]);
