@@ -74,6 +74,64 @@ def unit_flag(mla, args):
     return {"auto": 0, "fine": mla.UNIT_FINE, "coarse": mla.UNIT_COARSE}[args.unit]
 
 
+def lds_patterns():
+    """(name, op, 64 byte offsets) of the main kernel's three LDS access patterns (op 0 ds_read_b128: the K operand,
+    2 ds_read_b64_tr_b16: the V^T operand, 1 ds_write_b128: the tile write) for candidate row strides and token orders.
+    Lane l = 16 g + r16.  Rows are 1152 bytes of data, `stride` bytes apart."""
+    lanes = range(64)
+    pats = [("ds_read_b128, 64 lanes x 16 B contiguous (reference)", 0, [16 * l for l in lanes]),
+            ("ds_write_b128, 64 lanes x 16 B contiguous (reference)", 1, [16 * l for l in lanes]),
+            ("ds_read_b64_tr_b16, 64 lanes x 8 B contiguous (reference)", 2, [8 * l for l in lanes])]
+    even_odd = lambda r: ((2 * r) & 15) + (r >> 3)
+    for stride in (1152, 1168, 1184, 1200, 1216, 1248):
+        pats.append(("K operand: lane -> row r16, chunk g; row stride %d" % stride, 0, [(l & 15) * stride + 16 * (l >> 4) for l in lanes]))
+    pats.append(("K operand: lane -> row 2 r16 mod 16 + (r16 >= 8) (even rows first), chunk g; row stride 1168", 0,
+                 [even_odd(l & 15) * 1168 + 16 * (l >> 4) for l in lanes]))
+    for d in (0, 16, 32, 64, 256):
+        pats.append(("K operand, row stride 1168, groups %d bytes apart instead of 16" % d, 0, [(l & 15) * 1168 + d * (l >> 4) for l in lanes]))
+    for stride in (1168, 1184):
+        for ct in (0, 1, 5):
+            pats.append(("V^T operand: quad q of k-group g -> row 4 g + q, value tile %d; row stride %d" % (ct, stride), 2,
+                         [(4 * (l >> 4) + ((l & 15) >> 2)) * stride + (l & 3) * 8 + 32 * ct for l in lanes]))
+    pats.append(("V^T operand: rows 8 (g & 1) + (g >> 1) + 2 q (even rows first), value tile 0; row stride 1168", 2,
+                 [(8 * ((l >> 4) & 1) + (l >> 5) + 2 * ((l & 15) >> 2)) * 1168 + (l & 3) * 8 for l in lanes]))
+    pats.append(("V^T operand: rows 8 (g & 1) + (g >> 1) + 2 q (even rows first), value tile 0; row stride 1184", 2,
+                 [(8 * ((l >> 4) & 1) + (l >> 5) + 2 * ((l & 15) >> 2)) * 1184 + (l & 3) * 8 for l in lanes]))
+    for stride in (1168, 1184):
+        for i in (0, 1, 4, 8):
+            pats.append(("tile write: load %d of 36 (lane l holds 16-byte chunk 64 i + l of the tile); row stride %d" % (i, stride), 1,
+                         [((64 * i + l) // 72) * stride + 16 * ((64 * i + l) % 72) for l in lanes]))
+    # the direct orientation (comparison kernel) reads K and V as above; its P crosses lanes through LDS, heads `ps` floats apart
+    for ps in (32, 36, 40):
+        pats.append(("direct orientation, P to LDS: ds_write_b32 at float (4 g + i) %d + r16" % ps, 3, [((4 * (l >> 4)) * ps + (l & 15)) * 4 for l in lanes]))
+        pats.append(("direct orientation, P from LDS: ds_read_b128 at float %d r16 + 4 g" % ps, 0, [((l & 15) * ps + 4 * (l >> 4)) * 4 for l in lanes]))
+    return pats
+
+
+def lds_probe(torch, dev):
+    """One launch of the LDS probe kernel per pattern of lds_patterns(), in order; prints the patterns' names as one
+    JSON line, so that a rocprofv3 --pmc run of this mode can be read dispatch by dispatch."""
+    import ctypes
+    from paper_2506_01969_amd import build as hip_build
+    if not os.path.exists(hip_build.LDS_PROBE_LIB_PATH):
+        hip_build.build_lds_probe()
+    lib = ctypes.CDLL(hip_build.LDS_PROBE_LIB_PATH)
+    lib.lds_probe_run.argtypes = [ctypes.c_void_p, ctypes.c_int, ctypes.c_void_p, ctypes.c_void_p]
+    lib.lds_probe_run.restype = ctypes.c_int
+    sink = torch.zeros((16,), dtype=torch.int32, device=dev)
+    names = []
+    for name, op, offs in lds_patterns():
+        assert len(offs) == 64 and all(o % 4 == 0 and 0 <= o <= 40 * 1024 - 16 for o in offs), name
+        table = torch.tensor(offs, dtype=torch.int32, device=dev)
+        rc = lib.lds_probe_run(ctypes.c_void_p(table.data_ptr()), op, ctypes.c_void_p(sink.data_ptr()),
+                               ctypes.c_void_p(torch.cuda.current_stream(dev).cuda_stream))
+        if rc != 0:
+            raise RuntimeError("lds_probe_run failed")
+        torch.cuda.synchronize()
+        names.append(name)
+    print(json.dumps({"lds_probe_patterns_in_dispatch_order": names, "iterations_per_launch": 4096}))
+
+
 def timeline(torch, inputs, dev, args):
     """Where the time of one call goes, from the measurement build of the library (the product source compiled
     with -DMLA_TIMELINE: every wavefront of the main kernel and every block of the merge kernel record the
@@ -219,6 +277,9 @@ def main():
     ap.add_argument("--timeline", action="store_true",
                     help="per-phase time stamps of one call of --config from the measurement build of the library "
                          "(medians over --steps calls), as one JSON line; then exit")
+    ap.add_argument("--lds-probe", action="store_true",
+                    help="only launch the LDS access-pattern probe once per pattern (the main kernel's K, V^T and tile-write "
+                         "patterns for candidate row strides; for rocprofv3 --pmc SQ_LDS_BANK_CONFLICT SQ_LDS_IDX_ACTIVE) and exit")
     ap.add_argument("--ceiling-probe", action="store_true",
                     help="only run the plain streaming-read probe (no arithmetic, the main kernel's request pattern) over "
                          "the KV buffers of --config for several numbers of workgroups, print one JSON line each and exit")
@@ -249,6 +310,10 @@ def main():
         torch.cuda.synchronize()
         print(json.dumps({"copy_calibration_bytes_read": src.numel() * 4, "copy_calibration_bytes_written": src.numel() * 4,
                           "copies": 5}))
+        return
+
+    if args.lds_probe:
+        lds_probe(torch, dev)
         return
 
     if args.sweep:

@@ -13,6 +13,9 @@ LIB_PATH = os.path.join(_HERE, "libmla_decode.so")
 TIMELINE_LIB_PATH = os.path.join(_HERE, "libmla_decode_timeline.so")
 PROBE_SOURCES = [os.path.join(_HERE, "csrc", "hbm_probe.hip")]
 PROBE_LIB_PATH = os.path.join(_HERE, "libhbm_probe.so")
+# measurement only: one LDS access pattern per launch, for the bank-conflict counters (bench.py --lds-probe)
+LDS_PROBE_SOURCES = [os.path.join(_HERE, "csrc", "lds_probe.hip")]
+LDS_PROBE_LIB_PATH = os.path.join(_HERE, "liblds_probe.so")
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
@@ -46,6 +49,11 @@ def build_timeline(verbose: bool = False) -> str:
     return _compile(SOURCES, TIMELINE_LIB_PATH, verbose, extra=["-DMLA_TIMELINE"])
 
 
+def build_lds_probe(verbose: bool = False) -> str:
+    """The LDS access-pattern probe of the benchmark (measurement only).  Returns the library path."""
+    return _compile(LDS_PROBE_SOURCES, LDS_PROBE_LIB_PATH, verbose)
+
+
 def build_probe(verbose: bool = False) -> str:
     """The streaming-read probe of the benchmark (measurement only).  Returns the library path."""
     return _compile(PROBE_SOURCES, PROBE_LIB_PATH, verbose)
@@ -55,3 +63,4 @@ if __name__ == "__main__":
     print(build_library(verbose=True))
     print(build_probe(verbose=True))
     print(build_timeline(verbose=True))
+    print(build_lds_probe(verbose=True))

@@ -78,8 +78,10 @@ static_assert(kRowBytes == mla_plan::kRowBytes && kTile == mla_plan::kTileRows &
 constexpr int kKSteps = kDqk / 32;           // 18 MFMA k-steps over the 576 dims
 constexpr int kDvTiles = kDv / 16;           // 32 output tiles of 16 value columns
 constexpr int kStatsOff = kWaves * kWaveLds; // m and l of the 4 wavefronts live after the tiles
-constexpr int kRescaleOff = kStatsOff + 2 * kWaves * kHeads * 4;  // 2 KB per wavefront, cold rescale path
-constexpr int kLdsBytes = kRescaleOff + kWaves * 2048;
+constexpr int kRescaleOff = kStatsOff + 2 * kWaves * kHeads * 4;  // a slot per wavefront: cold rescale path (2 KB), P of the direct orientation
+constexpr int kPStride = 36;                 // floats between the heads of P in that slot (direct orientation): 4 mod 16, see there
+constexpr int kSlotBytes = kHeads * kPStride * 4;   // 2304
+constexpr int kLdsBytes = kRescaleOff + kWaves * kSlotBytes;
 static_assert(kLdsBytes <= 160 * 1024, "LDS of one compute unit");
 static_assert(kWaves * kTile == MLA_UNIT_TOKENS && mla_plan::kUnitCoarse == MLA_UNIT_TOKENS && mla_plan::kUnitFine == MLA_UNIT_TOKENS_FINE,
               "header and kernel disagree on the scheduling units");
@@ -333,22 +335,18 @@ __global__ void __launch_bounds__(kThreads, 1) mla_decode_split_kernel(const Par
     //   V^T operand, ds_read_b64_tr_b16: a cycle serves 32 lanes = eight rows x 32 bytes; with this stride
     //     rows 4g + q (q = the lane's quad) of k-groups g = 0, 1 and of g = 2, 3 tile the 64 banks exactly.
     //   tile write, ds_write_b128: conflict-free for every position of the row boundary inside a load.
-    // So token t of a 16-token score block simply sits on MFMA position t in the transposed orientation.
-    // The direct orientation reads rows by token position 8g .. 8g+3 and 8g+4 .. 8g+7 (its P operand is
-    // transposed across lanes), and position t holds token tau(t) = t xor 4 (t / 8): the first read of
-    // k-groups 0, 1 then takes rows 0..3 and 12..15, the second rows 4..7 and 8..11, eight rows that differ mod 8.
-    const int k_row = kDirect ? (r16 ^ ((r16 & 8) >> 1)) : r16;
+    // So token t of a 16-token score block simply sits on MFMA position t, in both orientations; the
+    // contraction index 8g + i of the second product stands for token 4g + i (i < 4) or 16 + 4g + i - 4.
+    const int k_row = r16;
     const int k_off = k_row * kLdsRow + g * 16;           // K operand: token k_row (+16), chunk 4*kk + g
-    // V^T operand through the transposing read: within each 16-lane group, lane j points at
-    // row j/4, columns 4*(j%4)..+3 of a 4x16 block and receives column j, rows 0..3.
-    // Tokens of the two reads, in the order of the other operand's 8 k-values: transposed
-    // orientation 4g .. 4g+3 and 16 more; direct orientation tau(8g) .. tau(8g+3) (in the second half
-    // of the tile for g >= 2) and tau(8g+4) .. tau(8g+7), four rows further on (g even) or back (g odd)
-    const int v_row = kDirect ? 16 * (g >> 1) + 12 * (g & 1) + (r16 >> 2) : 4 * g + (r16 >> 2);
+    // V^T operand (direct orientation: V) through the transposing read: within each 16-lane group,
+    // lane j points at row j/4, columns 4*(j%4)..+3 of a 4x16 block and receives column j, rows 0..3.
+    // Tokens of the two reads, in the order of the other operand's 8 k-values: 4g .. 4g+3 and 16 more.
+    const int v_row = 4 * g + (r16 >> 2);
     const int v_off = v_row * kLdsRow + (r16 & 3) * 8;
-    const int v_second = kDirect ? ((g & 1) ? -4 : 4) * kLdsRow : 16 * kLdsRow;
+    constexpr int kVSecond = 16 * kLdsRow;
     // direct orientation: P crosses lanes as fp32 [16 heads][32 tokens], in the rescale path's slot
-    float *p_tr = reinterpret_cast<float *>(smem + kRescaleOff + w * 2048);
+    float *p_tr = reinterpret_cast<float *>(smem + kRescaleOff + w * kSlotBytes);
     float *stat_m = reinterpret_cast<float *>(smem + kStatsOff);
     float *stat_l = stat_m + kWaves * kHeads;
     const unsigned lane16 = (unsigned)l * 16;               // global-load lane offsets (bytes)
@@ -539,21 +537,22 @@ __global__ void __launch_bounds__(kThreads, 1) mla_decode_split_kernel(const Par
                             alpha[i] = __builtin_amdgcn_exp2f(m4[i] - m_new);
                             m4[i] = m_new;
                         }
-                        rescale_accumulators(o, alpha, smem + kRescaleOff + w * 2048 + l * 16);
+                        rescale_accumulators(o, alpha, smem + kRescaleOff + w * kSlotBytes + l * 16);
                         l4 *= alpha;
                     }
                 }
-                // P[head 4g+i][token] -> LDS, then this lane takes head r16, tokens 8g .. 8g+7
+                // P[head 4g+i][token] -> LDS, then this lane takes head r16, tokens 4g .. 4g+3 and 16 more
 #pragma unroll
                 for (int i = 0; i < 4; ++i) {
                     const float p0 = __builtin_amdgcn_exp2f(x0[i] - m4[i]);
                     const float p1 = __builtin_amdgcn_exp2f(x1[i] - m4[i]);
                     l4[i] += p0 + p1;
-                    p_tr[(4 * g + i) * 32 + r16] = p0;
-                    p_tr[(4 * g + i) * 32 + 16 + r16] = p1;
+                    p_tr[(4 * g + i) * kPStride + r16] = p0;
+                    p_tr[(4 * g + i) * kPStride + 16 + r16] = p1;
                 }
-                const f32x4 lo4 = *reinterpret_cast<const f32x4 *>(p_tr + r16 * 32 + 8 * g);     // same wavefront:
-                const f32x4 hi4 = *reinterpret_cast<const f32x4 *>(p_tr + r16 * 32 + 8 * g + 4); // LDS keeps its order
+                // (heads 36 floats apart: the four k-groups' stores then fall on 64 distinct banks)
+                const f32x4 lo4 = *reinterpret_cast<const f32x4 *>(p_tr + r16 * kPStride + 4 * g);      // same wavefront:
+                const f32x4 hi4 = *reinterpret_cast<const f32x4 *>(p_tr + r16 * kPStride + 16 + 4 * g); // LDS keeps its order
 #pragma unroll
                 for (int i = 0; i < 4; ++i) {
                     pr[i] = lo4[i];
@@ -586,7 +585,7 @@ __global__ void __launch_bounds__(kThreads, 1) mla_decode_split_kernel(const Par
             } else if (__builtin_amdgcn_ballot_w64(mx > m_run + kLazyLog2) != 0) {
                 const float m_new = fmaxf(m_run, mx);
                 const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
-                rescale_accumulators(o, f32x4{alpha, alpha, alpha, alpha}, smem + kRescaleOff + w * 2048 + l * 16);
+                rescale_accumulators(o, f32x4{alpha, alpha, alpha, alpha}, smem + kRescaleOff + w * kSlotBytes + l * 16);
                 l_run *= alpha;
                 m_run = m_new;
             }
@@ -622,7 +621,7 @@ __global__ void __launch_bounds__(kThreads, 1) mla_decode_split_kernel(const Par
             // The transposing reads run kVAhead value tiles ahead of their MFMAs.
             {
                 i16x4 vb[kVAhead][2];
-                const char *rd_v2 = rd_v + v_second;      // the tile's other 16 rows (direct orientation: 4 rows on or back)
+                const char *rd_v2 = rd_v + kVSecond;      // the tile's other 16 rows
 #pragma unroll
                 for (int ct = 0; ct < kVAhead; ++ct) {
                     vb[ct][0] = read_tr16(rd_v + ct * 32);

@@ -78,6 +78,21 @@ def test_many_short_sequences(oracle, num_wg):
     _check(out, lse, ref_o, ref_l, label="many_short num_wg=%s" % num_wg)
 
 
+@pytest.mark.parametrize("num_wg", [None, 1000])
+def test_thousands_of_sequences(oracle, num_wg):
+    """Three thousand sequences of 0 ... 48 rows (47 chunks of 64 lengths for the wavefront-wide scans, a
+    dozen sequences per workgroup, empty ones throughout, a last chunk that is not full)."""
+    g = torch.Generator().manual_seed(99)
+    lens = torch.randint(0, 49, (3000,), generator=g).tolist()
+    for i in range(0, 3000, 7):
+        lens[i] = 0
+    q, kv, l = inputs.make_inputs(3000, 48, lens, seed=113, poison_tail=True)
+    ref_o, ref_l = _oracle(oracle, q, kv, l)
+    print("case thousands num_wg", num_wg, flush=True)
+    out, lse = _run(q, kv, l, num_wg=num_wg)
+    _check(out, lse, ref_o, ref_l, label="thousands num_wg=%s" % num_wg)
+
+
 def test_one_very_long_sequence(oracle):
     """A single sequence of 300,001 rows shared by every workgroup (176 pieces for the combine
     kernel to merge: more than one batch of its loads), next to a one-row sequence."""
