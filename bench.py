@@ -361,7 +361,6 @@ def main():
                        num_workgroups=nwg, phases=phases | orient)
 
     # ---- the practical ceiling: a plain streaming read of the same buffers ------------------------
-    # (measured first: its few hundred launches also take the GPU past the slower first launches of a process)
     ceiling = max(probe_ceiling(torch, kvs, launches=100), key=lambda r: r["gb_per_s"])
 
     # ---- main kernel alone, events on the launch stream (torch's current stream) ---------------
