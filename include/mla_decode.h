@@ -77,6 +77,18 @@ mla_status_t mla_decode_workspace_size(int batch, int num_heads, int max_seqlen_
                                        int *num_workgroups_used);
 
 /*
+ * The same size query for the automatic plan on a device of num_compute_units compute units, without
+ * touching any device (for callers that size buffers before a GPU is chosen, and for hosts without
+ * one): the bytes mla_decode_workspace_size(batch, num_heads, max_seqlen_kv, 0, ...) returns when the
+ * current device has that many compute units, and in *num_workgroups_used (may be NULL) the
+ * workgroups the automatic plan launches there for one query token per sequence.
+ * num_compute_units outside 1 .. 65536 is MLA_ERR_INVALID_ARG; other errors as above.
+ */
+mla_status_t mla_decode_workspace_size_for(int batch, int num_heads, int max_seqlen_kv,
+                                           int num_compute_units, size_t *bytes,
+                                           int *num_workgroups_used);
+
+/*
  * One decode-attention call.
  *
  *   q               device, bf16 [batch][1][16][576], contiguous, 16-byte aligned

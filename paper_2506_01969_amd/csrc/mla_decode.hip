@@ -1175,6 +1175,17 @@ mla_status_t mla_decode_workspace_size(int batch, int num_heads, int max_seqlen_
     return MLA_OK;
 }
 
+mla_status_t mla_decode_workspace_size_for(int batch, int num_heads, int max_seqlen_kv, int num_compute_units,
+                                           size_t *bytes, int *num_workgroups_used) {
+    if (!bytes) return MLA_ERR_INVALID_ARG;
+    mla_status_t st = check_shape(batch, num_heads, max_seqlen_kv);
+    if (st != MLA_OK) return st;
+    if (num_compute_units < 1 || num_compute_units > kMaxWorkgroups) return MLA_ERR_INVALID_ARG;
+    *bytes = mla_plan::workspace_bytes(batch, num_compute_units);      // covers the plan for any number of query tokens
+    if (num_workgroups_used) *num_workgroups_used = mla_plan::workgroups_for(batch, 1, max_seqlen_kv, num_compute_units);
+    return MLA_OK;
+}
+
 mla_status_t mla_decode_typed(const void *q, const void *kv_cache, int64_t kv_batch_stride,
                               const int32_t *cache_seqlens, int batch, int q_len, int num_heads,
                               int max_seqlen_kv, int dtype, float scale, float *out, float *lse,

@@ -47,6 +47,8 @@ def lib():
         szp, cip = ctypes.POINTER(ctypes.c_size_t), ctypes.POINTER(ctypes.c_int)
         L.mla_decode_workspace_size.argtypes = [ci, ci, ci, ci, szp, cip]
         L.mla_decode_workspace_size.restype = ci
+        L.mla_decode_workspace_size_for.argtypes = [ci, ci, ci, ci, szp, cip]
+        L.mla_decode_workspace_size_for.restype = ci
         L.mla_decode.argtypes = [vp, vp, ctypes.c_int64, vp, ci, ci, ci, ctypes.c_float, vp, vp, vp, sz, vp]
         L.mla_decode.restype = ci
         L.mla_decode_ex.argtypes = [vp, vp, ctypes.c_int64, vp, ci, ci, ci, ctypes.c_float, vp, vp,
@@ -74,6 +76,16 @@ def mla_decode_workspace_size(batch, num_heads, max_seqlen_kv, num_workgroups=0)
                                          ctypes.byref(nbytes), ctypes.byref(used))
     if st != MLA_OK:
         raise MlaError(st, "mla_decode_workspace_size")
+    return nbytes.value, used.value
+
+
+def mla_decode_workspace_size_for(batch, num_heads, max_seqlen_kv, num_compute_units):
+    """-> (bytes, num_workgroups_used) of the automatic plan on a device of that many compute units (host only)."""
+    nbytes, used = ctypes.c_size_t(0), ctypes.c_int(0)
+    st = lib().mla_decode_workspace_size_for(batch, num_heads, max_seqlen_kv, num_compute_units,
+                                             ctypes.byref(nbytes), ctypes.byref(used))
+    if st != MLA_OK:
+        raise MlaError(st, "mla_decode_workspace_size_for")
     return nbytes.value, used.value
 
 

@@ -20,8 +20,9 @@ def _declared_functions():
 
 def test_library_exports_every_declared_symbol():
     names = _declared_functions()
-    assert {"mla_decode", "mla_decode_ex", "mla_decode_typed", "mla_decode_workspace_size",
-            "mla_decode_planned_workgroups", "mla_status_string"} <= set(names)
+    assert {"mla_decode", "mla_decode_ex", "mla_decode_typed", "mla_decode_static", "mla_decode_workspace_size",
+            "mla_decode_workspace_size_for", "mla_decode_planned_workgroups", "mla_decode_plan_table",
+            "mla_status_string"} <= set(names)
     lib = mla.lib()
     for n in names:
         assert hasattr(lib, n), n
@@ -43,6 +44,23 @@ def test_workspace_size_is_two_slots_per_workgroup_one_per_sequence_plus_eight(b
     assert (2 * num_wg + batch + 8) * slot <= nbytes <= (2 * num_wg + batch + 8) * slot + 16
     # independent of the KV length: the lengths live on the device
     assert mla.mla_decode_workspace_size(batch, 16, 7, num_workgroups=num_wg) == (nbytes, used)
+
+
+def test_workspace_size_of_the_automatic_plan_without_a_device():
+    # the automatic plan for a device of 256 compute units: 208 workgroups for a long stream, 256 for a short
+    # one; the size covers 256 workgroups with two query tokens each, whatever the plan launches
+    slot = 16 * 512 * 4 + 16 * 4
+    for batch, seqlen, want_wg in ((16, 65536, 208), (16, 4096, 256), (1, 512, 256), (128, 65536, 208)):
+        nbytes, used = mla.mla_decode_workspace_size_for(batch, 16, seqlen, 256)
+        assert used == want_wg
+        assert nbytes == mla.mla_decode_workspace_size(batch, 16, seqlen, num_workgroups=256)[0]
+        assert (2 * 256 + batch + 8) * slot <= nbytes <= (2 * 256 + batch + 8) * slot + 16
+    assert mla.mla_decode_workspace_size_for(3, 16, 100, 1) == (mla.mla_decode_workspace_size(3, 16, 100, num_workgroups=1)[0], 1)
+    lib = mla.lib()
+    n = ctypes.c_size_t(0)
+    assert lib.mla_decode_workspace_size_for(16, 16, 4096, 0, ctypes.byref(n), None) == mla.MLA_ERR_INVALID_ARG
+    assert lib.mla_decode_workspace_size_for(16, 8, 4096, 256, ctypes.byref(n), None) == mla.MLA_ERR_UNSUPPORTED_SHAPE
+    assert lib.mla_decode_workspace_size_for(16, 16, 4096, 256, None, None) == mla.MLA_ERR_INVALID_ARG
 
 
 def test_workspace_size_errors():

@@ -653,3 +653,21 @@ def test_two_threads_on_two_streams_equal_the_serial_results():
         t.join(timeout=100)
     assert not any(t.is_alive() for t in threads)
     assert jobs[0]["bad"] == [] and jobs[1]["bad"] == []
+
+
+# ---- the other kernel variants at grid shapes: fp16 inputs and two query tokens -----------------------
+
+@pytest.mark.parametrize("batch,n", [(16, 4096), (32, 16384)])
+def test_figure_grid_fp16_and_two_tokens(oracle, batch, n):
+    """Two points of the Figure-1 grid with fp16 inputs (the paper's own precision) and with two query
+    tokens per sequence (Section 3.1), every output element against the oracle, automatic plan."""
+    print("case grid variants batch", batch, "kv", n, "fp16", flush=True)
+    q, kv, l = inputs.make_inputs(batch, n, None, seed=inputs.BASE_SEED + 300 + batch, dtype=torch.float16)
+    out, lse = _run(q, kv, l)
+    ref_o, ref_l = _oracle_f16(oracle, q, kv, l)
+    _check_f16(out, lse, ref_o, ref_l, "grid fp16 batch %d kv %d" % (batch, n), kv)
+    print("case grid variants batch", batch, "kv", n, "two tokens", flush=True)
+    q, kv, l = inputs.make_inputs(batch, n, None, seed=inputs.BASE_SEED + 400 + batch, q_len=2)
+    out, lse = _run_general(q, kv, l)
+    ref_o, ref_l = _oracle_general(oracle, q, kv, l, torch.bfloat16)
+    _check(out, lse, ref_o.reshape(-1, 16, inputs.D_V), ref_l.reshape(-1, 16), label="grid q_len 2 batch %d kv %d" % (batch, n))
