@@ -93,6 +93,26 @@ def test_thousands_of_sequences(oracle, num_wg):
     _check(out, lse, ref_o, ref_l, label="thousands num_wg=%s" % num_wg)
 
 
+def test_largest_number_of_workgroups(oracle):
+    """num_workgroups at its maximum (65536: a 4.3 GB workspace, a grid far larger than the unit stream,
+    so almost every workgroup finds no unit and leaves at once), with 32-row and with 128-row units."""
+    lens = [700, 0, 33, 1000, 129]
+    q, kv, l = inputs.make_inputs(len(lens), 1000, lens, seed=114, poison_tail=True)
+    ref_o, ref_l = _oracle(oracle, q, kv, l)
+    dev = _dev()
+    need, used = mla.mla_decode_workspace_size(len(lens), 16, 1000, 65536)
+    assert used == 65536
+    ws = torch.empty((need,), dtype=torch.uint8, device=dev)
+    for flags in (mla.UNIT_FINE, mla.UNIT_COARSE):
+        print("case largest grid flags", flags, flush=True)
+        out, lse = mla.mla_decode(q.to(dev), kv.to(dev), l.to(dev), inputs.SCALE, workspace=ws, num_workgroups=65536,
+                                  phases=mla.PHASE_SPLIT | mla.PHASE_COMBINE | flags)
+        torch.cuda.synchronize()
+        _check(out.cpu().numpy().reshape(len(lens), 16, 512).astype(np.float64), lse.cpu().numpy().astype(np.float64),
+               ref_o, ref_l, label="largest grid flags=%d" % flags)
+    del ws
+
+
 def test_one_very_long_sequence(oracle):
     """A single sequence of 300,001 rows shared by every workgroup (176 pieces for the combine
     kernel to merge: more than one batch of its loads), next to a one-row sequence."""
